@@ -1,0 +1,137 @@
+"""CPU oracle for the daBNN hot path (arXiv 1908.05858) -- TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader around ``dabnn_oracle.c`` (plain C + OpenMP).  Only ``tests/``,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
+package.  It imports nothing from the GPU package and the GPU package imports nothing from here.
+
+What each function computes, with the passage it follows, is stated in ``dabnn_oracle.c``:
+``sign`` / ``bitpack`` follow Sec. 2.1.1; ``bconv2d`` is the +-1 float cross-correlation that
+Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal; ``glue`` only generates inputs.
+
+Every function here is pinned by ``tests/test_oracle_pins.py`` (closed forms, invariants, brute
+force, torch's CPU conv2d, numpy.packbits); none is "parity unpinned".
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dabnn_oracle.c")
+_LIB_PATH = os.path.join(_HERE, "libdabnn_oracle.so")
+_lib = None
+
+SIGN_BIT = 0  # -1 iff the IEEE sign bit is set (Sec. 2.1.1)
+SIGN_GE0 = 1  # +1 iff x >= 0
+
+
+def build(force=False):
+    """Compile the oracle with gcc.  AVX2 baseline so one build runs on any host of this pool."""
+    if not force and os.path.exists(_LIB_PATH) and os.path.getmtime(_LIB_PATH) >= os.path.getmtime(_SRC):
+        return _LIB_PATH
+    cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fno-fast-math", "-std=c11", "-Wall",
+           "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB_PATH, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+    lib.oracle_sign.argtypes = [vp, vp, i64, i32]
+    lib.oracle_bitpack.argtypes = [vp, vp, i64, i32, i32]
+    lib.oracle_conv_out_dim.argtypes = [i32] * 4
+    lib.oracle_bconv2d.argtypes = [vp, vp, vp] + [i32] * 9
+    lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
+    lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
+    for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
+              lib.oracle_bconv2d_at, lib.oracle_glue):
+        f.restype = i32
+    _lib = lib
+    return lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle.{what}: bad argument (code {rc})")
+
+
+def sign(x, sign_rule=SIGN_BIT):
+    """+-1.0f tensor of the same shape as x (Sec. 2.1.1)."""
+    x = _f32(x)
+    s = np.empty_like(x)
+    _check(_load().oracle_sign(x.ctypes.data, s.ctypes.data, x.size, sign_rule), "sign")
+    return s
+
+
+def bitpack(x, sign_rule=SIGN_BIT):
+    """x: fp32 [..., C] -> uint64 [..., ceil(C/64)], LSB-first, tail bits 0 (Sec. 2.1.1)."""
+    x = _f32(x)
+    C = x.shape[-1]
+    words = (C + 63) // 64
+    n_pixels = x.size // C if C else 0
+    out = np.empty(x.shape[:-1] + (words,), dtype=np.uint64)
+    _check(_load().oracle_bitpack(x.ctypes.data, out.ctypes.data, n_pixels, C, sign_rule), "bitpack")
+    return out
+
+
+def conv_out_dim(size, k, stride, pad):
+    return _load().oracle_conv_out_dim(size, k, stride, pad)
+
+
+def bconv2d_signed(A, Wt, stride=1, pad=0):
+    """+-1 float cross-correlation, out-of-image taps = +1.  A: [N,H,W,Cin], Wt: [Cout,kh,kw,Cin]
+    (values +-1.0f) -> int32 [N,Ho,Wo,Cout]  (Sec. 2.1.2, Eq. 6-7)."""
+    A, Wt = _f32(A), _f32(Wt)
+    N, H, W, Cin = A.shape
+    Cout, kh, kw, Cin2 = Wt.shape
+    if Cin != Cin2:
+        raise ValueError("channel mismatch")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    Y = np.empty((N, Ho, Wo, Cout), dtype=np.int32)
+    _check(_load().oracle_bconv2d(A.ctypes.data, Wt.ctypes.data, Y.ctypes.data, N, H, W, Cin, Cout,
+                                  kh, kw, stride, pad), "bconv2d")
+    return Y
+
+
+def bconv2d(x, w, stride=1, pad=0, sign_rule=SIGN_BIT):
+    """The whole operator on raw fp32 tensors: binarize both, then convolve."""
+    return bconv2d_signed(sign(x, sign_rule), sign(w, sign_rule), stride, pad)
+
+
+def bconv2d_at(A, Wt, idx, stride=1, pad=0):
+    """Selected outputs of bconv2d_signed: idx int32 [S,4] rows (n,ho,wo,co) -> int32 [S]."""
+    A, Wt = _f32(A), _f32(Wt)
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 4)
+    N, H, W, Cin = A.shape
+    Cout, kh, kw, Cin2 = Wt.shape
+    if Cin != Cin2:
+        raise ValueError("channel mismatch")
+    out = np.empty(idx.shape[0], dtype=np.int32)
+    _check(_load().oracle_bconv2d_at(A.ctypes.data, Wt.ctypes.data, idx.ctypes.data, idx.shape[0],
+                                     out.ctypes.data, N, H, W, Cin, Cout, kh, kw, stride, pad),
+           "bconv2d_at")
+    return out
+
+
+def glue(x, y, gamma, beta, K, stride):
+    """Input generator for the next layer of the full-network workload (not the method)."""
+    x, gamma, beta = _f32(x), _f32(gamma), _f32(beta)
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    N, H, W, Cin = x.shape
+    _, Ho, Wo, Cout = y.shape
+    out = np.empty(y.shape, dtype=np.float32)
+    _check(_load().oracle_glue(x.ctypes.data, y.ctypes.data, gamma.ctypes.data, beta.ctypes.data,
+                               out.ctypes.data, N, H, W, Cin, Ho, Wo, Cout, K, stride), "glue")
+    return out

@@ -1,0 +1,280 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something that is NOT the
+oracle -- closed forms, invariants, brute force over Python ints, numpy.packbits, torch's CPU
+conv2d.  The paper prints no worked numeric example for this path (its only packing example is a
+figure), so these pins are what fixes the oracle.  No GPU is used.
+
+Each pin is aimed at one plausible mistake: a dropped tap, a wrong padding value, a flipped
+kernel, a transposed weight layout, a wrong bit order, a wrong sign convention at +-0.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1908_05858_amd import workloads as wl
+
+
+def popcount(v):
+    return bin(int(v)).count("1")
+
+
+# ----------------------------------------------------------------------------- sign / packer
+
+def test_sign_rules_on_special_values(oracle):
+    x = wl.special_values()
+    bits = x.view(np.uint32)
+    s0 = oracle.sign(x, oracle.SIGN_BIT)
+    # Sec. 2.1.1: the binary value is the IEEE sign bit, nothing else.
+    assert np.array_equal(s0, np.where(bits >> 31 == 1, -1.0, 1.0).astype(np.float32))
+    s1 = oracle.sign(x, oracle.SIGN_GE0)
+    expect = []
+    for v in x.tolist():
+        expect.append(1.0 if v >= 0 else -1.0)  # Python float compare: -0.0 >= 0, NaN fails
+    assert np.array_equal(s1, np.array(expect, dtype=np.float32))
+    # the two rules differ exactly at -0.0 and at positive NaN
+    differ = s0 != s1
+    for i in np.nonzero(differ)[0]:
+        assert bits[i] == 0x80000000 or (np.isnan(x[i]) and bits[i] >> 31 == 0)
+
+
+def test_bitpack_matches_numpy_packbits(oracle):
+    rng = np.random.default_rng(7)
+    for C in (1, 3, 63, 64, 65, 80, 128, 200, 256):
+        x = rng.standard_normal((5, 3, C)).astype(np.float32)
+        x = wl.inject_zeros(x, 11 + C, frac=0.05)
+        got = oracle.bitpack(x)
+        words = (C + 63) // 64
+        assert got.shape == (5, 3, words) and got.dtype == np.uint64
+        sb = np.signbit(x)
+        padded = np.zeros((5, 3, words * 64), dtype=bool)
+        padded[..., :C] = sb
+        ref = np.packbits(padded, axis=-1, bitorder="little").view("<u8")
+        assert np.array_equal(got, ref)
+        # popcount of all words == number of negative-signed elements
+        assert sum(popcount(v) for v in got.ravel()) == int(sb.sum())
+
+
+def test_bitpack_one_hot_and_tail(oracle):
+    for C in (64, 80, 200):
+        words = (C + 63) // 64
+        x = np.ones((C, C), dtype=np.float32)
+        x[np.arange(C), np.arange(C)] = -1.0  # pixel p has only channel p negative
+        got = oracle.bitpack(x)
+        for p in range(C):
+            for j in range(words):
+                want = (1 << (p % 64)) if j == p // 64 else 0
+                assert int(got[p, j]) == want
+        # all-negative row: exactly C low bits set, tail bits zero
+        allneg = oracle.bitpack(-np.ones((1, C), dtype=np.float32))
+        val = sum(int(allneg[0, j]) << (64 * j) for j in range(words))
+        assert val == (1 << C) - 1
+
+
+def test_bitpack_negation_complements(oracle):
+    rng = np.random.default_rng(3)
+    C = 200
+    x = rng.standard_normal((4, C)).astype(np.float32)
+    a, b = oracle.bitpack(x), oracle.bitpack(-x)
+    for p in range(4):
+        va = sum(int(a[p, j]) << (64 * j) for j in range(4))
+        vb = sum(int(b[p, j]) << (64 * j) for j in range(4))
+        assert va ^ vb == (1 << C) - 1
+
+
+def test_bitpack_sign_rule_ge0(oracle):
+    x = np.array([[0.0, -0.0, 1.0, -1.0, np.nan, -np.nan, np.inf, -np.inf]], dtype=np.float32)
+    assert int(oracle.bitpack(x, oracle.SIGN_BIT)[0, 0]) == 0b10101010
+    # x >= 0 rule: -0.0 becomes +1 (bit 0), both NaNs become -1 (bit 1)
+    assert int(oracle.bitpack(x, oracle.SIGN_GE0)[0, 0]) == 0b10111000
+
+
+def test_packed_size_is_one_32nd(oracle):
+    # Sec. 3: packing compresses binary weights 32x
+    w = wl.weights((64, 3, 3, 128), 5)
+    assert oracle.bitpack(w).nbytes * 32 == w.nbytes
+
+
+# ----------------------------------------------------------------------------- convolution
+
+SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (1, 5, 6, 3, 4, 3, 1, 1),
+    (2, 7, 7, 64, 8, 3, 2, 1),
+    (1, 6, 5, 80, 5, 3, 1, 0),
+    (1, 4, 4, 7, 3, 1, 1, 0),
+    (1, 9, 8, 5, 2, 3, 2, 0),
+    (1, 5, 5, 2, 3, 5, 1, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_closed_forms_plus_minus_K(oracle, shape):
+    N, H, W, Cin, Cout, k, s, p = shape
+    K = k * k * Cin
+    ones_a = np.ones((N, H, W, Cin), np.float32)
+    ones_w = np.ones((Cout, k, k, Cin), np.float32)
+    # all-equal -> +K everywhere, borders included because padding taps are +1
+    assert np.all(oracle.bconv2d_signed(ones_a, ones_w, s, p) == K)
+    # activations +1, weights -1 -> -K everywhere
+    assert np.all(oracle.bconv2d_signed(ones_a, -ones_w, s, p) == -K)
+    # activations -1, weights +1: -K + 2*t*Cin with t = number of taps outside the image
+    y = oracle.bconv2d_signed(-ones_a, ones_w, s, p)
+    Ho, Wo = y.shape[1:3]
+    for ho in range(Ho):
+        for wo in range(Wo):
+            t = 0
+            for i in range(k):
+                for j in range(k):
+                    hi, wi = ho * s - p + i, wo * s - p + j
+                    t += not (0 <= hi < H and 0 <= wi < W)
+            assert np.all(y[:, ho, wo, :] == -K + 2 * t * Cin)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_parity_bound_and_negation(oracle, shape):
+    N, H, W, Cin, Cout, k, s, p = shape
+    K = k * k * Cin
+    A = oracle.sign(wl.activations((N, H, W, Cin), 21))
+    Wt = wl.weights((Cout, k, k, Cin), 22)
+    y = oracle.bconv2d_signed(A, Wt, s, p)
+    assert y.dtype == np.int32
+    assert np.all((y - K) % 2 == 0)          # outputs keep the parity of K
+    assert np.all(np.abs(y) <= K)
+    assert np.array_equal(oracle.bconv2d_signed(A, -Wt, s, p), -y)  # linear in the weights
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_all_plus_weights_count_negatives(oracle, shape):
+    """W == +1 -> y = K - 2 * (#negative activations in the window), counted with an integral
+    image of numpy.signbit, independently of any multiply-add."""
+    N, H, W, Cin, Cout, k, s, p = shape
+    x = wl.activations((N, H, W, Cin), 31)
+    K = k * k * Cin
+    neg = np.signbit(x).sum(axis=-1).astype(np.int64)            # [N,H,W]
+    padded = np.zeros((N, H + 2 * p, W + 2 * p), np.int64)
+    padded[:, p:p + H, p:p + W] = neg
+    ii = np.zeros((N, H + 2 * p + 1, W + 2 * p + 1), np.int64)
+    ii[:, 1:, 1:] = padded.cumsum(1).cumsum(2)
+    y = oracle.bconv2d(x, np.ones((Cout, k, k, Cin), np.float32), s, p)
+    Ho, Wo = y.shape[1:3]
+    for ho in range(Ho):
+        for wo in range(Wo):
+            r0, c0 = ho * s, wo * s
+            cnt = ii[:, r0 + k, c0 + k] - ii[:, r0, c0 + k] - ii[:, r0 + k, c0] + ii[:, r0, c0]
+            assert np.array_equal(y[:, ho, wo, 0], K - 2 * cnt)
+            assert np.all(y[:, ho, wo, :] == y[:, ho, wo, :1])
+
+
+@pytest.mark.parametrize("shape", SHAPES + [(2, 14, 14, 64, 64, 3, 1, 1), (1, 14, 14, 128, 32, 3, 2, 1)])
+def test_against_torch_cpu_conv2d(oracle, shape):
+    """Library routine: fp32 conv2d on +-1 tensors is exact (integers below 2^24)."""
+    N, H, W, Cin, Cout, k, s, p = shape
+    A = oracle.sign(wl.activations((N, H, W, Cin), 41))
+    Wt = wl.weights((Cout, k, k, Cin), 42, p_plus=0.3)
+    y = oracle.bconv2d_signed(A, Wt, s, p)
+    a_t = torch.from_numpy(A).permute(0, 3, 1, 2).contiguous()
+    a_t = torch.nn.functional.pad(a_t, (p, p, p, p), value=1.0)
+    w_t = torch.from_numpy(Wt).permute(0, 3, 1, 2).contiguous()
+    ref = torch.nn.functional.conv2d(a_t, w_t, stride=s).permute(0, 2, 3, 1).contiguous()
+    assert np.array_equal(y, ref.numpy().astype(np.int32))
+
+
+def _brute_conv(a, w, H, W, Cin, Cout, k, s, p):
+    """Ten-line definition over Python ints; a[h][w][c], w[co][i][j][c] in {+1,-1}."""
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    out = [[[0] * Cout for _ in range(Wo)] for _ in range(Ho)]
+    for ho, wo, co in itertools.product(range(Ho), range(Wo), range(Cout)):
+        acc = 0
+        for i, j, c in itertools.product(range(k), range(k), range(Cin)):
+            hi, wi = ho * s - p + i, wo * s - p + j
+            av = a[hi][wi][c] if (0 <= hi < H and 0 <= wi < W) else 1
+            acc += av * w[co][i][j][c]
+        out[ho][wo][co] = acc
+    return out
+
+
+@pytest.mark.parametrize("H,W,Cin,k,s,p", [(2, 2, 2, 3, 1, 1), (3, 3, 1, 3, 2, 1), (2, 3, 2, 1, 1, 0),
+                                          (3, 2, 1, 3, 1, 1)])
+def test_brute_force_all_activation_patterns(oracle, H, W, Cin, k, s, p):
+    """Every one of the 2^(H*W*Cin) activation sign patterns, against the Python-int definition."""
+    Cout = 2
+    nbits = H * W * Cin
+    assert nbits <= 12
+    wt = wl.weights((Cout, k, k, Cin), 51 + nbits)
+    wl_list = wt.astype(int).tolist()
+    pats = np.array(list(itertools.product([1.0, -1.0], repeat=nbits)), np.float32)
+    A = pats.reshape(len(pats), H, W, Cin)
+    y = oracle.bconv2d_signed(A, wt, s, p)
+    for n in range(len(pats)):
+        ref = _brute_conv(A[n].astype(int).tolist(), wl_list, H, W, Cin, Cout, k, s, p)
+        assert y[n].tolist() == ref
+
+
+def test_brute_force_all_weight_patterns(oracle):
+    """Every 2^9 weight pattern of a 3x3x1 filter on a fixed non-symmetric image: catches a
+    flipped kernel or swapped kh/kw axes."""
+    H, W, Cin, k, s, p = 4, 3, 1, 3, 1, 1
+    x = wl.activations((1, H, W, Cin), 61)
+    A = oracle.sign(x)
+    pats = np.array(list(itertools.product([1.0, -1.0], repeat=9)), np.float32)
+    Wt = pats.reshape(len(pats), k, k, Cin)
+    y = oracle.bconv2d_signed(A, Wt, s, p)          # Cout = 512
+    ref = _brute_conv(A[0].astype(int).tolist(), Wt.astype(int).tolist(), H, W, Cin, len(pats), k, s, p)
+    assert y[0].tolist() == ref
+
+
+@pytest.mark.parametrize("Cin", [3, 64, 80, 200])
+def test_xor_popcount_identity(oracle, Cin):
+    """Eq. 1 / Eq. 6 with Python big ints: y = K - 2*popcount(a XOR w) over the packed window,
+    where a and w come from the oracle's packer and out-of-image taps are zero words.  Ties the
+    float oracle to the bit formula the GPU implements."""
+    N, H, W, Cout, k, s, p = 1, 5, 4, 3, 3, 1, 1
+    x = wl.inject_zeros(wl.activations((N, H, W, Cin), 71), 72, frac=0.05)
+    wf = wl.weights((Cout, k, k, Cin), 73)
+    y = oracle.bconv2d(x, wf, s, p)
+    ap, wp = oracle.bitpack(x), oracle.bitpack(wf)
+    words = ap.shape[-1]
+    K = k * k * Cin
+    for ho, wo, co in itertools.product(range(y.shape[1]), range(y.shape[2]), range(Cout)):
+        diff = 0
+        for i, j in itertools.product(range(k), range(k)):
+            hi, wi = ho * s - p + i, wo * s - p + j
+            for q in range(words):
+                av = int(ap[0, hi, wi, q]) if (0 <= hi < H and 0 <= wi < W) else 0
+                diff += popcount(av ^ int(wp[co, i, j, q]))
+        assert int(y[0, ho, wo, co]) == K - 2 * diff
+
+
+def test_bconv2d_at_matches_full(oracle):
+    N, H, W, Cin, Cout, k, s, p = 2, 9, 7, 80, 6, 3, 2, 1
+    A = oracle.sign(wl.activations((N, H, W, Cin), 81))
+    Wt = wl.weights((Cout, k, k, Cin), 82)
+    y = oracle.bconv2d_signed(A, Wt, s, p)
+    idx = np.array(list(itertools.product(range(N), range(y.shape[1]), range(y.shape[2]), range(Cout))),
+                   np.int32)
+    assert np.array_equal(oracle.bconv2d_at(A, Wt, idx, s, p), y.ravel())
+
+
+def test_out_dim_and_bad_args(oracle):
+    assert oracle.conv_out_dim(56, 3, 1, 1) == 56
+    assert oracle.conv_out_dim(56, 3, 2, 1) == 28
+    assert oracle.conv_out_dim(7, 3, 2, 1) == 4
+    assert oracle.conv_out_dim(2, 3, 1, 0) < 0
+    with pytest.raises(ValueError):
+        oracle.bconv2d_signed(np.ones((1, 2, 2, 3), np.float32), np.ones((1, 3, 3, 4), np.float32), 1, 1)
+
+
+def test_glue_closed_form(oracle):
+    """The input generator: stride 1 adds x itself; stride 2 adds the 2x2 mean, channels repeated."""
+    N, H, W, C = 1, 4, 4, 2
+    x = np.arange(N * H * W * C, dtype=np.float32).reshape(N, H, W, C)
+    y = np.zeros((N, H, W, C), np.int32)
+    g, b = np.ones(C, np.float32), np.zeros(C, np.float32)
+    assert np.array_equal(oracle.glue(x, y, g, b, 4, 1), x)
+    y[...] = 2
+    out = oracle.glue(x, y, 3 * g, b + 1, 4, 1)
+    assert np.allclose(out, 3 * 2 / 2 + 1 + x)
+    y2 = np.zeros((N, 2, 2, 2 * C), np.int32)
+    out2 = oracle.glue(x, y2, np.ones(2 * C, np.float32), np.zeros(2 * C, np.float32), 4, 2)
+    pooled = x.reshape(N, 2, 2, 2, 2, C).mean(axis=(2, 4))
+    assert np.allclose(out2, np.concatenate([pooled, pooled], axis=-1))
