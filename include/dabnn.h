@@ -1,0 +1,110 @@
+/*
+ * dabnn.h -- C ABI of the MI355X (gfx950) bit-packing + binary direct convolution library.
+ *
+ * The operations are the two binary operators of daBNN (arXiv 1908.05858): bit-packing of the
+ * sign of fp32 tensors (Sec. 2.1.1) and binary convolution computed as popcounts of XORed
+ * bit-vectors (Sec. 2.1.2, Eq. 1 and Eq. 6-7), with weights packed ahead of time (Sec. 3).
+ *
+ * Conventions common to every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees, copies to the host or synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates
+ *     its arguments on the host, enqueues its kernel(s) on `stream` and returns at once.
+ *   - Return value: a dabnn_status (0 = DABNN_OK).  On any error nothing is launched and no
+ *     output byte is written.  No exception crosses the boundary.
+ *   - Tensors are dense, row-major, in the layouts stated per call.  Input and output buffers
+ *     of one call must not overlap.
+ *   - Bit convention (shared by activations and weights): bit 1 <-> value -1, bit 0 <-> +1;
+ *     channel c lives in 64-bit word c/64 at bit c%64 (least significant bit first); bits past
+ *     the last channel of a pixel are 0.
+ */
+#ifndef DABNN_H
+#define DABNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DABNN_OK = 0,
+    DABNN_ERR_NULL = 1,        /* a required pointer is NULL */
+    DABNN_ERR_SHAPE = 2,       /* a size is <= 0, inconsistent, or too large for int32 indexing */
+    DABNN_ERR_ALIGN = 3,       /* fp32/int32 buffer not 4-byte or packed buffer not 8-byte aligned */
+    DABNN_ERR_UNSUPPORTED = 4, /* unknown sign_mode / algo, or algo cannot run this shape */
+    DABNN_ERR_LAUNCH = 5       /* the HIP runtime refused the launch */
+} dabnn_status;
+
+typedef enum {
+    DABNN_SIGN_BIT = 0, /* Sec. 2.1.1: the bit is the IEEE-754 sign bit (-0.0 -> -1, NaN by its sign) */
+    DABNN_SIGN_GE0 = 1  /* the bit is !(x >= 0): -0.0 -> +1, every NaN -> -1 */
+} dabnn_sign_mode;
+
+typedef enum {
+    DABNN_ALGO_AUTO = 0,      /* fastest kernel that supports the shape */
+    DABNN_ALGO_REFERENCE = 1, /* one thread per output, any shape; the GPU-side safety net */
+    DABNN_ALGO_WREG = 2,      /* weights resident in VGPRs, activations broadcast through SGPRs;
+                                 3x3 kernels with ceil(Cin/64) in {1,2,4,8}, stride 1 or 2 */
+    DABNN_ALGO_WLDS = 3       /* weights staged in LDS, activations broadcast through SGPRs; any
+                                 kernel size whose packed 64-filter slice fits in LDS */
+} dabnn_algo;
+
+/* ceil(C / 64): 64-bit words per pixel for C channels.  Returns -1 if C <= 0. */
+int64_t dabnn_packed_words(int64_t C);
+
+/* Output extent of a convolution: floor((in + 2*pad - k) / stride) + 1, or -1 if the arguments
+ * are invalid (in, k, stride <= 0, pad < 0, pad >= k, or in + 2*pad < k). */
+int dabnn_conv_out_dim(int in, int k, int stride, int pad);
+
+/*
+ * Sign + bit-packing of an activation tensor (Sec. 2.1.1).
+ *   x   : fp32  [n_pixels][C]              (NHWC with N*H*W flattened into n_pixels), read only
+ *   out : u64   [n_pixels][ceil(C/64)]     written completely, tail bits 0
+ * n_pixels may be 0: nothing is launched and the pointers are not looked at.
+ * n_pixels * C must be < 2^40.
+ */
+int dabnn_bitpack(const float *x, uint64_t *out, int64_t n_pixels, int C, int sign_mode,
+                  void *stream);
+
+/*
+ * Ahead-of-time packing of binary-convolution weights (Sec. 3), same bit rule as above.
+ *   w   : fp32 [Cout][kh][kw][Cin], any values (only the sign is used), read only
+ *   out : u64  [Cout][kh][kw][ceil(Cin/64)]   -- the canonical packed weight layout
+ */
+int dabnn_pack_weights(const float *w, uint64_t *out, int Cout, int kh, int kw, int Cin,
+                       int sign_mode, void *stream);
+
+/*
+ * Binary direct convolution (Sec. 2.1.2, Eq. 6-7; cross-correlation, no kernel flip).
+ *   a : u64 [N][H][W][Cw]        packed activations, Cw = ceil(Cin/64), tail bits 0
+ *   w : u64 [Cout][kh][kw][Cw]   packed weights (canonical layout), tail bits 0
+ *   y : i32 [N][Ho][Wo][Cout]    Ho = dabnn_conv_out_dim(H, kh, stride, pad), same for Wo
+ *
+ *   y[n,ho,wo,co] = K - 2 * sum_{i,j,q} popcount(a[n, ho*stride-pad+i, wo*stride-pad+j, q]
+ *                                              XOR w[co,i,j,q]),      K = kh*kw*Cin,
+ * i.e. 2C - K with C the match count of Eq. 1.  A tap outside the image counts as an all-zero
+ * word (every channel +1).  Tail bits must be 0 in both operands (true for buffers produced by
+ * dabnn_bitpack / dabnn_pack_weights); they then cancel and K counts real channels only.
+ * Requires 0 <= pad < min(kh, kw), stride >= 1, and every tensor below 2^31 elements.
+ */
+int dabnn_bconv2d(const uint64_t *a, const uint64_t *w, int32_t *y, int N, int H, int W, int Cin,
+                  int Cout, int kh, int kw, int stride, int pad, void *stream);
+
+/* Same operation with the kernel family chosen by the caller (a dabnn_algo).  Returns
+ * DABNN_ERR_UNSUPPORTED, launching nothing, if that family cannot run the shape. */
+int dabnn_bconv2d_algo(const uint64_t *a, const uint64_t *w, int32_t *y, int N, int H, int W,
+                       int Cin, int Cout, int kh, int kw, int stride, int pad, int algo,
+                       void *stream);
+
+/* Which dabnn_algo DABNN_ALGO_AUTO resolves to for this shape (no launch). */
+int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,
+                            int pad);
+
+/* Human-readable name of a dabnn_status; static storage, never NULL. */
+const char *dabnn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DABNN_H */

@@ -1,0 +1,125 @@
+"""ctypes binding of libdabnn.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory) and enqueues the library's kernels on
+torch's current stream.  There is no CPU path: if the HIP library is missing or the tensors are
+not on the GPU, the call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdabnn.so")
+
+SIGN_BIT, SIGN_GE0 = 0, 1
+ALGO_AUTO, ALGO_REFERENCE, ALGO_WREG, ALGO_WLDS = 0, 1, 2, 3
+
+_lib = None
+
+
+class DabnnError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+
+
+def load():
+    """Load libdabnn.so (built beforehand by ``__graft_entry__.build()`` / ``build.py``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+    lib.dabnn_packed_words.argtypes, lib.dabnn_packed_words.restype = [i64], i64
+    lib.dabnn_conv_out_dim.argtypes, lib.dabnn_conv_out_dim.restype = [i32] * 4, i32
+    lib.dabnn_bitpack.argtypes, lib.dabnn_bitpack.restype = [vp, vp, i64, i32, i32, vp], i32
+    lib.dabnn_pack_weights.argtypes, lib.dabnn_pack_weights.restype = [vp, vp] + [i32] * 5 + [vp], i32
+    lib.dabnn_bconv2d.argtypes, lib.dabnn_bconv2d.restype = [vp] * 3 + [i32] * 9 + [vp], i32
+    lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
+    lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
+    lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
+           "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string"]
+
+
+def status_string(status):
+    return load().dabnn_status_string(int(status)).decode()
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda):
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise DabnnError(rc, what)
+
+
+def packed_words(C):
+    return load().dabnn_packed_words(C)
+
+
+def conv_out_dim(size, k, stride, pad):
+    return load().dabnn_conv_out_dim(size, k, stride, pad)
+
+
+def bitpack(x, out=None, sign_mode=SIGN_BIT):
+    """x: fp32 [..., C] on the GPU -> int64 tensor [..., ceil(C/64)] holding the u64 words."""
+    C = x.shape[-1]
+    n_pixels = x.numel() // C if C else 0
+    words = (C + 63) // 64
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (words,), dtype=torch.int64, device=x.device)
+    _check(load().dabnn_bitpack(_dev(x, torch.float32, "x"), _dev(out, torch.int64, "out"),
+                                n_pixels, C, sign_mode, _stream()), "dabnn_bitpack")
+    return out
+
+
+def pack_weights(w, out=None, sign_mode=SIGN_BIT):
+    """w: fp32 [Cout, kh, kw, Cin] -> int64 [Cout, kh, kw, ceil(Cin/64)] (canonical layout)."""
+    Cout, kh, kw, Cin = w.shape
+    if out is None:
+        out = torch.empty((Cout, kh, kw, (Cin + 63) // 64), dtype=torch.int64, device=w.device)
+    _check(load().dabnn_pack_weights(_dev(w, torch.float32, "w"), _dev(out, torch.int64, "out"),
+                                     Cout, kh, kw, Cin, sign_mode, _stream()), "dabnn_pack_weights")
+    return out
+
+
+def bconv2d(a, w, Cin, stride=1, pad=0, out=None, algo=ALGO_AUTO):
+    """a: int64 [N,H,W,Cw], w: int64 [Cout,kh,kw,Cw] (packed) -> int32 [N,Ho,Wo,Cout]."""
+    N, H, W, Cw = a.shape
+    Cout, kh, kw, Cw2 = w.shape
+    if Cw != Cw2 or Cw != (Cin + 63) // 64:
+        raise ValueError("packed word counts do not match Cin")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, Cout), dtype=torch.int32, device=a.device)
+    args = (_dev(a, torch.int64, "a"), _dev(w, torch.int64, "w"), _dev(out, torch.int32, "out"),
+            N, H, W, Cin, Cout, kh, kw, stride, pad)
+    if algo == ALGO_AUTO:
+        rc = load().dabnn_bconv2d(*args, _stream())
+    else:
+        rc = load().dabnn_bconv2d_algo(*args, algo, _stream())
+    _check(rc, "dabnn_bconv2d")
+    return out
+
+
+def pick_algo(N, H, W, Cin, Cout, kh, kw, stride, pad):
+    return load().dabnn_bconv2d_pick_algo(N, H, W, Cin, Cout, kh, kw, stride, pad)

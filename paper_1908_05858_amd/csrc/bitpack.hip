@@ -1,0 +1,128 @@
+// Sign + bit-packing of fp32 rows into 64-bit words (Sec. 2.1.1), for gfx950 wave64.
+//
+// The paper gathers sign bits with ARM's shift-right-insert so that many elements are packed
+// per instruction and no element is compared with zero.  The wave64 equivalent used here: lane i
+// of a wavefront loads channel 64*j + i of a pixel (one fully coalesced 256-byte read per
+// wavefront), and ONE vector compare on the raw fp32 bits writes all 64 sign bits into a scalar
+// register pair -- that pair already is the packed word, least significant bit = lowest channel.
+// Sixteen such words are built per wavefront from sixteen independent loads in flight, moved
+// into lanes 0..15 with a lane select, and stored as one contiguous 128-byte write.
+//
+// The kernel is bound by HBM reads: 4 bytes read and 1/8 byte written per element.
+#include "launch.h"
+
+#include <type_traits>
+
+namespace dabnn {
+namespace {
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+
+constexpr int kWordsPerWave = 16;
+constexpr int kWavesPerBlock = 4;
+
+// Bit value (1 <-> -1) from the raw fp32 bits, integer-only so that denormal flushing modes
+// cannot change the result.
+template <int MODE>
+__device__ __forceinline__ bool negative_bit(uint32_t u)
+{
+    if (MODE == 0)
+        return static_cast<int32_t>(u) < 0;  // the IEEE sign bit itself
+    // !(x >= 0): any negative non-zero value (this includes NaNs with the sign set), or a NaN.
+    return (u > 0x80000000u) || ((u & 0x7fffffffu) > 0x7f800000u);
+}
+
+// FLAT: C is a multiple of 64, so word g covers the 64 consecutive floats starting at 64*g.
+template <int MODE, bool FLAT>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_kernel(
+    const uint32_t* __restrict__ x, uint2* __restrict__ out, int64_t n_words, int C, int Cw)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t g0 =
+        (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block) * kWordsPerWave;
+    if (g0 >= n_words)
+        return;
+
+    uint32_t v[kWordsPerWave];
+    if (FLAT) {
+        if (g0 + kWordsPerWave <= n_words) {
+            const uint32_t* src = x + g0 * 64 + lane;
+#pragma unroll
+            for (int k = 0; k < kWordsPerWave; ++k)
+                v[k] = __builtin_nontemporal_load(src + k * 64);
+        } else {
+#pragma unroll
+            for (int k = 0; k < kWordsPerWave; ++k)
+                v[k] = (g0 + k < n_words) ? x[(g0 + k) * 64 + lane] : 0u;
+        }
+    } else {
+        int64_t p = g0 / Cw;
+        int j = static_cast<int>(g0 - p * Cw);
+#pragma unroll
+        for (int k = 0; k < kWordsPerWave; ++k) {
+            const int c = 64 * j + lane;
+            const bool valid = (g0 + k < n_words) && (c < C);
+            v[k] = valid ? x[p * C + c] : 0u;  // a missing channel packs as bit 0
+            if (++j == Cw) {
+                j = 0;
+                ++p;
+            }
+        }
+    }
+
+    uint32_t lo = 0, hi = 0;
+    static_for<0, kWordsPerWave>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        // the 64 sign bits of word k, wave-uniform; lane k keeps them for the store
+        const uint64_t word = __builtin_amdgcn_ballot_w64(negative_bit<MODE>(v[k]));
+        if (lane == k) {
+            lo = static_cast<uint32_t>(word);
+            hi = static_cast<uint32_t>(word >> 32);
+        }
+    });
+    if (lane < kWordsPerWave && g0 + lane < n_words)
+        out[g0 + lane] = make_uint2(lo, hi);
+}
+
+}  // namespace
+
+hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, int sign_mode,
+                          hipStream_t stream)
+{
+    const int64_t Cw = (static_cast<int64_t>(C) + 63) / 64;
+    const int64_t n_words = n_rows * Cw;
+    if (n_words == 0)
+        return hipSuccess;
+    const int64_t per_block = static_cast<int64_t>(kWordsPerWave) * kWavesPerBlock;
+    const int64_t blocks = (n_words + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL)
+        return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(64 * kWavesPerBlock);
+    const uint32_t* xi = reinterpret_cast<const uint32_t*>(x);
+    uint2* o = reinterpret_cast<uint2*>(out);
+    const bool flat = (C % 64) == 0;
+    const int cw = static_cast<int>(Cw);
+    if (sign_mode == 0) {
+        if (flat)
+            bitpack_kernel<0, true><<<grid, block, 0, stream>>>(xi, o, n_words, C, cw);
+        else
+            bitpack_kernel<0, false><<<grid, block, 0, stream>>>(xi, o, n_words, C, cw);
+    } else {
+        if (flat)
+            bitpack_kernel<1, true><<<grid, block, 0, stream>>>(xi, o, n_words, C, cw);
+        else
+            bitpack_kernel<1, false><<<grid, block, 0, stream>>>(xi, o, n_words, C, cw);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace dabnn

@@ -1,0 +1,164 @@
+// C ABI of the library (see include/dabnn.h): argument validation, error codes, dispatch.
+// Nothing here computes; every step of the path runs in the kernels of bitpack.hip / bconv.hip.
+#include "../../include/dabnn.h"
+
+#include "launch.h"
+
+namespace {
+
+bool aligned(const void* p, uintptr_t a)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+int out_dim(int in, int k, int stride, int pad)
+{
+    if (in <= 0 || k <= 0 || stride <= 0 || pad < 0 || pad >= k || in + 2 * pad < k)
+        return -1;
+    return (in + 2 * pad - k) / stride + 1;
+}
+
+constexpr int64_t kMaxElems = 0x7fffffffLL;  // every tensor is indexed with 32-bit element counts
+
+int make_shape(dabnn::ConvShape& s, int N, int H, int W, int Cin, int Cout, int kh, int kw,
+               int stride, int pad)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride <= 0 ||
+        pad < 0)
+        return DABNN_ERR_SHAPE;
+    if (pad >= kh || pad >= kw)
+        return DABNN_ERR_SHAPE;
+    const int Ho = out_dim(H, kh, stride, pad), Wo = out_dim(W, kw, stride, pad);
+    if (Ho <= 0 || Wo <= 0)
+        return DABNN_ERR_SHAPE;
+    const int64_t Cw = (static_cast<int64_t>(Cin) + 63) / 64;
+    const int64_t K = static_cast<int64_t>(kh) * kw * Cin;
+    if (K >= (1LL << 30))
+        return DABNN_ERR_SHAPE;
+    if (static_cast<int64_t>(N) * H * W * Cw > kMaxElems ||
+        static_cast<int64_t>(Cout) * kh * kw * Cw > kMaxElems ||
+        static_cast<int64_t>(N) * Ho * Wo * Cout > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    s = dabnn::ConvShape{N, H, W, Cin, Cout, kh, kw, stride, pad, Ho, Wo, static_cast<int>(Cw),
+                         static_cast<int>(K)};
+    return DABNN_OK;
+}
+
+int pick_algo(const dabnn::ConvShape& s)
+{
+    if (dabnn::bconv_wreg_supports(s))
+        return DABNN_ALGO_WREG;
+    if (dabnn::bconv_wlds_supports(s))
+        return DABNN_ALGO_WLDS;
+    return DABNN_ALGO_REFERENCE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t dabnn_packed_words(int64_t C)
+{
+    return C <= 0 ? -1 : (C + 63) / 64;
+}
+
+int dabnn_conv_out_dim(int in, int k, int stride, int pad)
+{
+    return out_dim(in, k, stride, pad);
+}
+
+int dabnn_bitpack(const float* x, uint64_t* out, int64_t n_pixels, int C, int sign_mode,
+                  void* stream)
+{
+    if (n_pixels < 0 || C <= 0 || n_pixels > (1LL << 40) / C)
+        return DABNN_ERR_SHAPE;
+    if (n_pixels == 0)
+        return DABNN_OK;  // nothing to do; empty tensors may have NULL storage
+    if (!x || !out)
+        return DABNN_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(out, 8))
+        return DABNN_ERR_ALIGN;
+    if (sign_mode != DABNN_SIGN_BIT && sign_mode != DABNN_SIGN_GE0)
+        return DABNN_ERR_UNSUPPORTED;
+    const hipError_t e =
+        dabnn::launch_bitpack(x, out, n_pixels, C, sign_mode, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_pack_weights(const float* w, uint64_t* out, int Cout, int kh, int kw, int Cin,
+                       int sign_mode, void* stream)
+{
+    if (!w || !out)
+        return DABNN_ERR_NULL;
+    if (Cout <= 0 || kh <= 0 || kw <= 0 || Cin <= 0)
+        return DABNN_ERR_SHAPE;
+    const int64_t rows = static_cast<int64_t>(Cout) * kh * kw;
+    if (rows > kMaxElems || rows * Cin > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    if (!aligned(w, 4) || !aligned(out, 8))
+        return DABNN_ERR_ALIGN;
+    if (sign_mode != DABNN_SIGN_BIT && sign_mode != DABNN_SIGN_GE0)
+        return DABNN_ERR_UNSUPPORTED;
+    // A filter tap is one "pixel" of Cin channels: the canonical layout is the packer's output.
+    const hipError_t e =
+        dabnn::launch_bitpack(w, out, rows, Cin, sign_mode, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_bconv2d_algo(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H, int W,
+                       int Cin, int Cout, int kh, int kw, int stride, int pad, int algo,
+                       void* stream)
+{
+    if (!a || !w || !y)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (!aligned(a, 8) || !aligned(w, 8) || !aligned(y, 4))
+        return DABNN_ERR_ALIGN;
+    if (algo == DABNN_ALGO_AUTO)
+        algo = pick_algo(s);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (algo) {
+        case DABNN_ALGO_REFERENCE: e = dabnn::launch_bconv_reference(a, w, y, s, st); break;
+        case DABNN_ALGO_WREG: e = dabnn::launch_bconv_wreg(a, w, y, s, st); break;
+        case DABNN_ALGO_WLDS: e = dabnn::launch_bconv_wlds(a, w, y, s, st); break;
+        default: return DABNN_ERR_UNSUPPORTED;
+    }
+    if (e == hipErrorNotSupported)
+        return DABNN_ERR_UNSUPPORTED;
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_bconv2d(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H, int W, int Cin,
+                  int Cout, int kh, int kw, int stride, int pad, void* stream)
+{
+    return dabnn_bconv2d_algo(a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad, DABNN_ALGO_AUTO,
+                              stream);
+}
+
+int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,
+                            int pad)
+{
+    dabnn::ConvShape s;
+    if (make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad) != DABNN_OK)
+        return -1;
+    return pick_algo(s);
+}
+
+const char* dabnn_status_string(int status)
+{
+    switch (status) {
+        case DABNN_OK: return "ok";
+        case DABNN_ERR_NULL: return "null pointer";
+        case DABNN_ERR_SHAPE: return "invalid shape";
+        case DABNN_ERR_ALIGN: return "misaligned pointer";
+        case DABNN_ERR_UNSUPPORTED: return "unsupported mode, algorithm or shape";
+        case DABNN_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

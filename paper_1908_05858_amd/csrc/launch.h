@@ -1,0 +1,30 @@
+// Internal launch interface between the C ABI (dabnn_api.hip) and the kernel files.
+// Arguments are already validated when these are called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dabnn {
+
+struct ConvShape {
+    int N, H, W, Cin, Cout, kh, kw, stride, pad;
+    int Ho, Wo, Cw;   // derived: output extent, 64-bit words per pixel
+    int K;            // kh*kw*Cin, true bit count under one output
+};
+
+// Sign + pack rows of C fp32 values into ceil(C/64) words each (Sec. 2.1.1).
+hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, int sign_mode,
+                          hipStream_t stream);
+
+// Binary convolution kernels (Sec. 2.1.2, Eq. 6-7).  Each returns hipErrorNotSupported, without
+// launching, when the family cannot run the shape.
+hipError_t launch_bconv_reference(const uint64_t* a, const uint64_t* w, int32_t* y,
+                                  const ConvShape& s, hipStream_t stream);
+hipError_t launch_bconv_wreg(const uint64_t* a, const uint64_t* w, int32_t* y,
+                             const ConvShape& s, hipStream_t stream);
+hipError_t launch_bconv_wlds(const uint64_t* a, const uint64_t* w, int32_t* y,
+                             const ConvShape& s, hipStream_t stream);
+bool bconv_wreg_supports(const ConvShape& s);
+bool bconv_wlds_supports(const ConvShape& s);
+
+}  // namespace dabnn

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, bit-exactly.
+
+Integer outputs and packed words are unique, so every comparison is `==` with zero tolerance.
+Inputs are the seeded synthetic tensors of `workloads`; expected values always come from
+`oracle/`, never from the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1908_05858_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dabnn():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests need a real MI355X")
+    from paper_1908_05858_amd import binding
+    binding.load()
+    return binding
+
+
+def gpu(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def words(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+# ------------------------------------------------------------------------------- bit-pack
+
+@pytest.mark.parametrize("shape", wl.CFG3_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("mode", [0, 1])
+def test_bitpack_cfg3(dabnn, oracle, shape, mode):
+    if mode == 1 and np.prod(shape) > 5e7:
+        pytest.skip("largest tensor is covered with the default sign rule")
+    print("bitpack", shape, "mode", mode, flush=True)
+    x = wl.inject_zeros(wl.activations(shape, wl.seed_for(3, shape[-1] + shape[0])), wl.seed_for(3, 1))
+    got = words(dabnn.bitpack(gpu(x), sign_mode=mode))
+    want = oracle.bitpack(x, mode)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("C", [1, 3, 63, 64, 65, 80, 127, 128, 200, 256, 1000])
+@pytest.mark.parametrize("n_pixels", [1, 5, 63, 64, 1025])
+def test_bitpack_ragged(dabnn, oracle, C, n_pixels):
+    print("bitpack ragged", C, n_pixels, flush=True)
+    x = wl.inject_zeros(wl.activations((n_pixels, C), 1000 + C + n_pixels), 17, frac=0.05)
+    for mode in (0, 1):
+        # guard words on both sides of the output catch out-of-bounds writes
+        Cw = (C + 63) // 64
+        buf = torch.full((n_pixels * Cw + 16,), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+        out = buf[8:8 + n_pixels * Cw].view(n_pixels, Cw)
+        dabnn.bitpack(gpu(x), out=out, sign_mode=mode)
+        assert np.array_equal(words(out), oracle.bitpack(x, mode))
+        assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
+
+
+def test_bitpack_special_values(dabnn, oracle):
+    row = wl.special_values()
+    x = np.tile(row, (3, 13))[:, :200].copy()       # C = 200: specials in every word, with a tail
+    for mode in (0, 1):
+        assert np.array_equal(words(dabnn.bitpack(gpu(x), sign_mode=mode)), oracle.bitpack(x, mode))
+
+
+def test_bitpack_empty(dabnn):
+    x = torch.empty((0, 64), dtype=torch.float32, device="cuda")
+    assert dabnn.bitpack(x).shape == (0, 1)
+
+
+def test_pack_weights(dabnn, oracle):
+    for shape in [(64, 3, 3, 64), (128, 3, 3, 80), (5, 1, 1, 200), (7, 5, 5, 3), (512, 3, 3, 512)]:
+        w = wl.weights(shape, 77 + shape[0], p_plus=0.3)
+        assert np.array_equal(words(dabnn.pack_weights(gpu(w))), oracle.bitpack(w))
+
+
+# ------------------------------------------------------------------------------- convolution
+
+def run_conv(dabnn, oracle, N, H, W, Cin, Cout, k, stride, pad, seed, algo, p_plus=0.5):
+    x = wl.activations((N, H, W, Cin), seed)
+    wf = wl.weights((Cout, k, k, Cin), seed + 1, p_plus)
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    Ho, Wo = oracle.conv_out_dim(H, k, stride, pad), oracle.conv_out_dim(W, k, stride, pad)
+    # guard values around the output catch out-of-bounds writes
+    n_out = N * Ho * Wo * Cout
+    buf = torch.full((n_out + 512,), -123456789, dtype=torch.int32, device="cuda")
+    out = buf[256:256 + n_out].view(N, Ho, Wo, Cout)
+    dabnn.bconv2d(a, wp, Cin, stride, pad, out=out, algo=algo)
+    want = oracle.bconv2d(x, wf, stride, pad)
+    got = out.cpu().numpy()
+    assert torch.all(buf[:256] == -123456789) and torch.all(buf[-256:] == -123456789)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} of {got.size} outputs differ, first at {bad[0]}: "
+                             f"got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}")
+
+
+ALGOS = [1, 2, 0]  # reference, weight-stationary, auto
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_cfg1_single_conv(dabnn, oracle, algo):
+    L = wl.CFG1_LAYER
+    run_conv(dabnn, oracle, 1, L.H, L.W, L.Cin, L.Cout, 3, 1, 1, wl.seed_for(1), algo)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("N", wl.CFG2_BATCHES)
+@pytest.mark.parametrize("li", range(4))
+def test_cfg2_stride1_sweep(dabnn, oracle, li, N, algo):
+    L = wl.CFG2_LAYERS[li]
+    print("cfg2", L, N, algo, flush=True)
+    run_conv(dabnn, oracle, N, L.H, L.W, L.Cin, L.Cout, 3, 1, 1, wl.seed_for(2, li), algo)
+
+
+@pytest.mark.parametrize("algo", [2, 0])
+@pytest.mark.parametrize("li", range(3))
+def test_cfg4_stride2(dabnn, oracle, li, algo):
+    L = wl.CFG4_LAYERS[li]
+    print("cfg4", L, algo, flush=True)
+    run_conv(dabnn, oracle, wl.CFG4_BATCH, L.H, L.W, L.Cin, L.Cout, 3, 2, 1, wl.seed_for(4, li), algo,
+             p_plus=wl.CFG4_P_PLUS)
+
+
+ODD_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (1, 1, 1, 1, 1, 1, 1, 0),
+    (2, 5, 7, 3, 5, 3, 1, 1),
+    (1, 9, 9, 63, 70, 3, 2, 1),
+    (3, 8, 6, 65, 64, 3, 1, 0),
+    (2, 13, 11, 80, 130, 3, 1, 1),
+    (1, 10, 17, 200, 33, 3, 2, 1),
+    (2, 6, 6, 128, 64, 1, 1, 0),
+    (1, 12, 12, 64, 16, 5, 1, 2),
+    (1, 7, 9, 100, 10, 3, 3, 1),
+    (2, 4, 30, 64, 64, 3, 1, 2),
+    (1, 3, 3, 512, 64, 3, 1, 1),
+    (5, 2, 2, 256, 192, 3, 2, 1),
+    (1, 33, 9, 64, 65, 3, 1, 1),
+    (1, 15, 15, 320, 8, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("algo", [1, 0])
+@pytest.mark.parametrize("shape", ODD_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_odd_shapes(dabnn, oracle, shape, algo):
+    print("odd", shape, algo, flush=True)
+    run_conv(dabnn, oracle, *shape, seed=4242 + sum(shape), algo=algo)
+
+
+@pytest.mark.parametrize("shape", [s for s in ODD_SHAPES if s[5] == 3 and s[6] in (1, 2) and
+                                   (s[3] + 63) // 64 in (1, 2, 4, 8)],
+                         ids=lambda s: "-".join(map(str, s)))
+def test_odd_shapes_wreg(dabnn, oracle, shape):
+    print("odd wreg", shape, flush=True)
+    run_conv(dabnn, oracle, *shape, seed=999 + sum(shape), algo=2)
+
+
+def test_closed_forms_on_gpu(dabnn):
+    """All-equal gives +K, all-opposite gives -K, with the border taps counted as +1."""
+    for (N, H, W, Cin, Cout, k, s, p) in [(2, 14, 14, 64, 64, 3, 1, 1), (1, 9, 9, 80, 70, 3, 2, 1)]:
+        K = k * k * Cin
+        ones_a = torch.ones((N, H, W, Cin), device="cuda")
+        ones_w = torch.ones((Cout, k, k, Cin), device="cuda")
+        a = dabnn.bitpack(ones_a)
+        for algo in (1, 0):
+            y = dabnn.bconv2d(a, dabnn.pack_weights(ones_w), Cin, s, p, algo=algo)
+            assert torch.all(y == K)
+            y = dabnn.bconv2d(a, dabnn.pack_weights(-ones_w), Cin, s, p, algo=algo)
+            assert torch.all(y == -K)
+
+
+def test_unsupported_algo_is_refused(dabnn):
+    a = torch.zeros((1, 4, 4, 1), dtype=torch.int64, device="cuda")
+    w = torch.zeros((4, 5, 5, 1), dtype=torch.int64, device="cuda")
+    with pytest.raises(dabnn.DabnnError) as e:
+        dabnn.bconv2d(a, w, 64, 1, 2, algo=dabnn.ALGO_WREG)   # 5x5 is not a wreg shape
+    assert e.value.status == 4
+
+
+# ------------------------------------------------------------------------------- full network
+
+def test_cfg5_chain_small_batch(dabnn, oracle):
+    """The sixteen-layer Bi-Real-18 body at its real shapes, batch 2, every layer compared in
+    full; the fp32 input of layer i+1 is generated by the oracle from the oracle's own y_i."""
+    N = 2
+    x = wl.activations((N, 56, 56, 64), wl.seed_for(5))
+    for li, L in enumerate(wl.BIREAL18_BODY):
+        print("cfg5 layer", li, L, flush=True)
+        wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li))
+        a_gpu = dabnn.bitpack(gpu(x))
+        assert np.array_equal(words(a_gpu), oracle.bitpack(x))
+        y_gpu = dabnn.bconv2d(a_gpu, dabnn.pack_weights(gpu(wf)), L.Cin, L.stride, 1)
+        y = oracle.bconv2d(x, wf, L.stride, 1)
+        assert np.array_equal(y_gpu.cpu().numpy(), y)
+        gamma, beta = wl.affine(L.Cout, wl.seed_for(5, li))
+        x = oracle.glue(x, y, gamma, beta, L.K, L.stride)
+
+
+@pytest.mark.parametrize("li", range(16))
+def test_cfg5_full_batch_layers(dabnn, oracle, li):
+    """Batch 256, the launch configuration the benchmark times.  Packed words are compared in
+    full; conv outputs on 200k sampled positions plus three whole images (first, middle, last)."""
+    L = wl.BIREAL18_BODY[li]
+    N = wl.CFG5_BATCH
+    print("cfg5 full", li, L, flush=True)
+    x = wl.activations((N, L.H, L.W, L.Cin), wl.seed_for(5, 100 + li))
+    wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li))
+    a_gpu = dabnn.bitpack(gpu(x))
+    assert np.array_equal(words(a_gpu), oracle.bitpack(x))
+    y_gpu = dabnn.bconv2d(a_gpu, dabnn.pack_weights(gpu(wf)), L.Cin, L.stride, 1).cpu().numpy()
+    A, Wt = oracle.sign(x), oracle.sign(wf)
+    rng = np.random.default_rng(li)
+    S = 200_000
+    idx = np.stack([rng.integers(0, N, S), rng.integers(0, L.Ho, S), rng.integers(0, L.Wo, S),
+                    rng.integers(0, L.Cout, S)], axis=1).astype(np.int32)
+    want = oracle.bconv2d_at(A, Wt, idx, L.stride, 1)
+    assert np.array_equal(y_gpu[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]], want)
+    for n in (0, N // 2, N - 1):
+        assert np.array_equal(y_gpu[n:n + 1], oracle.bconv2d_signed(A[n:n + 1], Wt, L.stride, 1))
+    # properties that hold at any size: parity of K and the bound |y| <= K
+    assert np.all((y_gpu - L.K) % 2 == 0) and np.abs(y_gpu).max() <= L.K
