@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: the sixteen binary 3x3 convolutions of a
+Bi-Real-Net-18 body at 224x224 input, batch 256, each preceded by the bit-pack of its fp32
+activation.  One step = 16 x (dabnn_bitpack + dabnn_bconv2d) over inputs resident in HBM.
+
+Prints ONE JSON line.  `value` is binary-convolution GOPS (2*K*Cout*Ho*Wo*N summed over the 16
+layers, divided by the wall time of a whole step, bit-packing included).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Peak of the plain-VALU path on MI355X, derived from the chip's unit counts and clock:
+# 256 CUs x 64 lanes/clk x 2.4 GHz = 39.32 T lane-ops/s; one v_xor_b32 + one v_bcnt_u32_b32
+# (popcount with fused accumulate) process 32 bits of one output, i.e. 64 counted binary ops per
+# 2 lane-ops => 32 ops per lane-op => 1258.29 TOP/s.
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 * 32 / 1e12
+HBM_PEAK_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=None, help="override the batch (default 256)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; batch sharding across GPUs is a design note "
+              "only (see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1908_05858_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    torch.cuda.set_device(0)
+    N = args.batch or wl.CFG5_BATCH
+    layers = wl.BIREAL18_BODY
+
+    # ---- inputs: seeded, synthetic, resident in HBM before any timing ---------------------
+    xs, wps, acts, ys = [], [], [], []
+    for li, L in enumerate(layers):
+        x = wl.activations((N, L.H, L.W, L.Cin), wl.seed_for(5, 100 + li))
+        xs.append(torch.from_numpy(x).cuda())
+        wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li))
+        wps.append(binding.pack_weights(torch.from_numpy(wf).cuda()))
+        acts.append(torch.empty((N, L.H, L.W, (L.Cin + 63) // 64), dtype=torch.int64, device="cuda"))
+        ys.append(torch.empty((N, L.Ho, L.Wo, L.Cout), dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+
+    def step(events=None, probe=-1):
+        """One pass of the hot path.  With `events`, layer `probe` of this step is bracketed by
+        three HIP events on the launch stream (before bit-pack, between, after the conv)."""
+        for li, L in enumerate(layers):
+            if li == probe:
+                events[0].record()
+            binding.bitpack(xs[li], out=acts[li])
+            if li == probe:
+                events[1].record()
+            binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li])
+            if li == probe:
+                events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps.  Step k carries HIP events (on the stream the kernels
+    # are launched on) around layer k mod 16 only, so every kernel launch of the step is sampled
+    # K/16 times while the instrumentation stays at three events per step.
+    all_events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(all_events[k], k % len(layers))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    pack_ms = np.zeros(len(layers))
+    conv_ms = np.zeros(len(layers))
+    samples = np.zeros(len(layers))
+    for k, ev in enumerate(all_events):
+        li = k % len(layers)
+        pack_ms[li] += ev[0].elapsed_time(ev[1])
+        conv_ms[li] += ev[1].elapsed_time(ev[2])
+        samples[li] += 1
+    if samples.min() == 0:
+        print("bench.py: --steps must be at least 16 so that every layer is sampled", file=sys.stderr)
+        sys.exit(2)
+    pack_ms /= samples
+    conv_ms /= samples
+
+    # the same K steps once more without the events, to show what the instrumentation costs
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for k in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t2) * 1e3 / args.steps
+
+    ops = [L.ops(N) for L in layers]
+    total_ops = float(sum(ops))
+    pack_bytes = [xs[li].numel() * 4 + acts[li].numel() * 8 for li in range(len(layers))]
+    conv_tops = total_ops / (conv_ms.sum() * 1e-3) / 1e12       # conv kernels only
+    pack_gbps = sum(pack_bytes) / (pack_ms.sum() * 1e-3) / 1e9  # bit-pack kernels only
+
+    per_layer = []
+    for li, L in enumerate(layers):
+        per_layer.append({
+            "layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}",
+            "bconv_us": round(conv_ms[li] * 1e3, 2),
+            "bconv_TOPs": round(ops[li] / (conv_ms[li] * 1e-3) / 1e12, 1),
+            "bitpack_us": round(pack_ms[li] * 1e3, 2),
+            "bitpack_GBps": round(pack_bytes[li] / (pack_ms[li] * 1e-3) / 1e9, 1),
+        })
+
+    result = {
+        "metric": "binary conv GOPS (2*K*Cout*Hout*Wout*N / s) + bitpack GB/s, % of roofline",
+        "value": round(total_ops / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64 packed bits, int32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": f"Bi-Real-Net-18 binary body, 224x224 input, batch {N}: 16 x (bitpack fp32 NHWC "
+                        "+ binary 3x3 conv), BASELINE.json configs[4]",
+            "batch": N,
+            "layers": len(layers),
+            "binary_ops_per_step": total_ops,
+        },
+        "ms_per_step_without_events": round(ms_plain, 4),
+        "event_samples_per_layer": int(samples.min()),
+        "bconv_only_GOPS": round(conv_tops * 1e3, 1),
+        "bconv_frac_of_valu_peak": round(conv_tops / VALU_PEAK_TOPS, 4),
+        "bitpack_GBps": round(pack_gbps, 1),
+        "bitpack_frac_of_hbm_peak": round(pack_gbps / HBM_PEAK_GBPS, 4),
+        "roofline": {
+            "kernel": "bconv (all 16 launches of dabnn_bconv2d in a step)",
+            "bound": "alu",
+            "achieved": round(conv_tops, 2),
+            "peak": round(VALU_PEAK_TOPS, 2),
+            "unit": "TOP/s",
+            "frac": round(conv_tops / VALU_PEAK_TOPS, 4),
+            "traffic": None,
+        },
+        "roofline_bitpack": {
+            "kernel": "bitpack (all 16 launches of dabnn_bitpack in a step)",
+            "bound": "hbm",
+            "achieved": round(pack_gbps, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(pack_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+        },
+        "per_layer": per_layer,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
+    if not args.no_cpu_baseline:
+        import oracle
+        n_img = N
+        cpu_x = [x.cpu().numpy() for x in xs]
+        cpu_w = [wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li)) for li, L in enumerate(layers)]
+        oracle.sign(cpu_x[0][:1])  # load the library and start the thread pool outside the timing
+        c0 = time.perf_counter()
+        passes = 0
+        while passes == 0 or (time.perf_counter() - c0 < 10.0 and passes < 8):
+            for li, L in enumerate(layers):
+                oracle.bitpack(cpu_x[li])
+                oracle.bconv2d_signed(oracle.sign(cpu_x[li]), oracle.sign(cpu_w[li]), L.stride, 1)
+            passes += 1
+        c1 = time.perf_counter()
+        cpu_ops = float(sum(L.ops(n_img) for L in layers)) * passes
+        threads = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+        result["cpu_baseline"] = {
+            "value": round(cpu_ops / (c1 - c0) / 1e9, 2),
+            "unit": "GOPS",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"the same 16 layers (sign + bit-pack + float +-1 conv) on all {n_img} images, "
+                      f"{passes} pass(es), {c1 - c0:.1f} s",
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,85 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol include/dabnn.h
+declares, and rejects bad arguments on the host without launching anything (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1908_05858_amd", "libdabnn.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_1908_05858_amd import build
+        build.build_library()
+    from paper_1908_05858_amd import binding
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dabnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dabnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert "dabnn_bitpack" in names and "dabnn_bconv2d" in names and "dabnn_pack_weights" in names
+    for name in names:
+        assert hasattr(lib, name), name
+    from paper_1908_05858_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_host_helpers(lib):
+    assert lib.dabnn_packed_words(1) == 1 and lib.dabnn_packed_words(64) == 1
+    assert lib.dabnn_packed_words(65) == 2 and lib.dabnn_packed_words(200) == 4
+    assert lib.dabnn_packed_words(0) == -1
+    assert lib.dabnn_conv_out_dim(56, 3, 1, 1) == 56
+    assert lib.dabnn_conv_out_dim(56, 3, 2, 1) == 28
+    assert lib.dabnn_conv_out_dim(7, 3, 2, 1) == 4
+    assert lib.dabnn_conv_out_dim(2, 3, 1, 0) == -1
+    assert lib.dabnn_conv_out_dim(5, 3, 1, 3) == -1
+    assert lib.dabnn_status_string(0) == b"ok"
+    assert lib.dabnn_status_string(99) == b"unknown status"
+
+
+def test_bad_arguments_are_refused_before_any_launch(lib):
+    P = ctypes.c_void_p
+    good, good8, odd = P(0x10000), P(0x20000), P(0x10002)
+    # bitpack
+    assert lib.dabnn_bitpack(P(0), good8, 4, 64, 0, None) == 1
+    assert lib.dabnn_bitpack(good, P(0), 4, 64, 0, None) == 1
+    assert lib.dabnn_bitpack(good, good8, -1, 64, 0, None) == 2
+    assert lib.dabnn_bitpack(good, good8, 4, 0, 0, None) == 2
+    assert lib.dabnn_bitpack(odd, good8, 4, 64, 0, None) == 3
+    assert lib.dabnn_bitpack(good, P(0x20004), 4, 64, 0, None) == 3
+    assert lib.dabnn_bitpack(good, good8, 4, 64, 7, None) == 4
+    assert lib.dabnn_bitpack(P(0), P(0), 0, 64, 0, None) == 0      # empty: nothing to do
+    # pack_weights
+    assert lib.dabnn_pack_weights(P(0), good8, 4, 3, 3, 64, 0, None) == 1
+    assert lib.dabnn_pack_weights(good, good8, 0, 3, 3, 64, 0, None) == 2
+    assert lib.dabnn_pack_weights(good, P(0x20004), 4, 3, 3, 64, 0, None) == 3
+    assert lib.dabnn_pack_weights(good, good8, 4, 3, 3, 64, 2, None) == 4
+    # bconv2d: (a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad, stream)
+    a, w, y = P(0x10000), P(0x20000), P(0x30000)
+    assert lib.dabnn_bconv2d(P(0), w, y, 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d(a, w, P(0), 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d(a, w, y, 0, 4, 4, 64, 8, 3, 3, 1, 1, None) == 2
+    assert lib.dabnn_bconv2d(a, w, y, 1, 4, 4, 64, 8, 3, 3, 0, 1, None) == 2   # stride 0
+    assert lib.dabnn_bconv2d(a, w, y, 1, 4, 4, 64, 8, 3, 3, 1, 3, None) == 2   # pad >= k
+    assert lib.dabnn_bconv2d(a, w, y, 1, 2, 2, 64, 8, 5, 5, 1, 0, None) == 2   # empty output
+    assert lib.dabnn_bconv2d(a, w, y, 1 << 20, 1 << 10, 1 << 10, 64, 8, 3, 3, 1, 1, None) == 2
+    assert lib.dabnn_bconv2d(P(0x10004), w, y, 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == 3
+    assert lib.dabnn_bconv2d(a, w, P(0x30002), 1, 4, 4, 64, 8, 3, 3, 1, 1, None) == 3
+    assert lib.dabnn_bconv2d_algo(a, w, y, 1, 4, 4, 64, 8, 3, 3, 1, 1, 9, None) == 4
+    assert lib.dabnn_bconv2d_algo(a, w, y, 1, 4, 4, 64, 8, 5, 5, 1, 2, 2, None) == 4  # wreg is 3x3 only
+
+
+def test_pick_algo(lib):
+    assert lib.dabnn_bconv2d_pick_algo(256, 56, 56, 64, 64, 3, 3, 1, 1) == 2
+    assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 5, 5, 1, 2) in (1, 3)
+    assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 3, 3, 0, 1) == -1
