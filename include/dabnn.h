@@ -46,8 +46,9 @@ typedef enum {
     DABNN_ALGO_REFERENCE = 1, /* one thread per output, any shape; the GPU-side safety net */
     DABNN_ALGO_WREG = 2,      /* weights resident in VGPRs, activations broadcast through SGPRs;
                                  3x3 kernels with ceil(Cin/64) in {1,2,4,8}, stride 1 or 2 */
-    DABNN_ALGO_WLDS = 3       /* weights staged in LDS, activations broadcast through SGPRs; any
-                                 kernel size whose packed 64-filter slice fits in LDS */
+    DABNN_ALGO_AREG = 3       /* each lane keeps one output pixel's 3x3 window in VGPRs, weights are
+                                 broadcast through SGPRs; 3x3 kernels with ceil(Cin/64) in
+                                 {1,2,4}, stride 1 or 2, Cout % 4 == 0, y 16-byte aligned */
 } dabnn_algo;
 
 /* ceil(C / 64): 64-bit words per pixel for C channels.  Returns -1 if C <= 0. */
@@ -97,7 +98,8 @@ int dabnn_bconv2d_algo(const uint64_t *a, const uint64_t *w, int32_t *y, int N, 
                        int Cin, int Cout, int kh, int kw, int stride, int pad, int algo,
                        void *stream);
 
-/* Which dabnn_algo DABNN_ALGO_AUTO resolves to for this shape (no launch). */
+/* Which dabnn_algo DABNN_ALGO_AUTO resolves to for this shape with a 16-byte aligned y (no
+ * launch); -1 if the shape is invalid. */
 int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,
                             int pad);
 

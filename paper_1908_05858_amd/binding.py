@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdabnn.so")
 
 SIGN_BIT, SIGN_GE0 = 0, 1
-ALGO_AUTO, ALGO_REFERENCE, ALGO_WREG, ALGO_WLDS = 0, 1, 2, 3
+ALGO_AUTO, ALGO_REFERENCE, ALGO_WREG, ALGO_AREG = 0, 1, 2, 3
 
 _lib = None
 

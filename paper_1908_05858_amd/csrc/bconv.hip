@@ -18,10 +18,8 @@
 //               bytes per pixel.  A wavefront walks P output pixels of one row at a time and
 //               loads each input column of the (P-1)*stride+3 wide window once per kernel row,
 //               which is the paper's window reuse with SGPRs in place of NEON registers.
+#include "kernel_util.h"
 #include "launch.h"
-
-#include <cstdlib>
-#include <type_traits>
 
 namespace dabnn {
 namespace {
@@ -118,26 +116,6 @@ __device__ __forceinline__ void xor_popc_acc(int& acc, const uint32_t* a, const 
 #pragma unroll
     for (int d = 0; d < D; d += NP)
         XorPopc<NP>::run(acc, a + d, w + d);
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
-// Wait until every scalar load issued so far has landed (lgkmcnt = 0, other counters untouched).
-__device__ __forceinline__ void wait_scalar_loads()
-{
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-}
-// Nothing may be moved across this point by the instruction scheduler.
-__device__ __forceinline__ void schedule_fence()
-{
-    __builtin_amdgcn_sched_barrier(0);
 }
 
 // Geometry of one task = P consecutive output pixels of one output row, for 64 output channels.
@@ -306,26 +284,6 @@ __global__ __launch_bounds__(256) void bconv3x3_wreg_kernel(
     }
 }
 
-int env_int(const char* name, int fallback)
-{
-    const char* e = std::getenv(name);
-    return e ? std::atoi(e) : fallback;
-}
-
-int device_cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0)
-            cus = 256;
-    }
-    return cus;
-}
-
 template <int CW, int S, int P>
 hipError_t launch_wreg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream)
@@ -418,17 +376,6 @@ hipError_t launch_bconv_wreg(const uint64_t* a, const uint64_t* w, int32_t* y, c
         case 4: return launch_wreg_s<4>(a32, w32, y, s, stream);
         default: return launch_wreg_s<8>(a32, w32, y, s, stream);
     }
-}
-
-bool bconv_wlds_supports(const ConvShape&)
-{
-    return false;
-}
-
-hipError_t launch_bconv_wlds(const uint64_t*, const uint64_t*, int32_t*, const ConvShape&,
-                             hipStream_t)
-{
-    return hipErrorNotSupported;
 }
 
 }  // namespace dabnn

@@ -9,22 +9,11 @@
 // into lanes 0..15 with a lane select, and stored as one contiguous 128-byte write.
 //
 // The kernel is bound by HBM reads: 4 bytes read and 1/8 byte written per element.
+#include "kernel_util.h"
 #include "launch.h"
-
-#include <type_traits>
 
 namespace dabnn {
 namespace {
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 
 constexpr int kWordsPerWave = 16;
 constexpr int kWavesPerBlock = 4;

@@ -44,12 +44,16 @@ int make_shape(dabnn::ConvShape& s, int N, int H, int W, int Cin, int Cout, int 
     return DABNN_OK;
 }
 
-int pick_algo(const dabnn::ConvShape& s)
+int pick_algo(const dabnn::ConvShape& s, const void* y)
 {
+    // Keep the larger operand in VGPRs and stream the smaller one through the scalar path:
+    // few words per pixel -> activation window stationary; many -> filter stationary.
+    if (s.Cw <= 2 && dabnn::bconv_areg_supports(s, y))
+        return DABNN_ALGO_AREG;
     if (dabnn::bconv_wreg_supports(s))
         return DABNN_ALGO_WREG;
-    if (dabnn::bconv_wlds_supports(s))
-        return DABNN_ALGO_WLDS;
+    if (dabnn::bconv_areg_supports(s, y))
+        return DABNN_ALGO_AREG;
     return DABNN_ALGO_REFERENCE;
 }
 
@@ -118,13 +122,13 @@ int dabnn_bconv2d_algo(const uint64_t* a, const uint64_t* w, int32_t* y, int N, 
     if (!aligned(a, 8) || !aligned(w, 8) || !aligned(y, 4))
         return DABNN_ERR_ALIGN;
     if (algo == DABNN_ALGO_AUTO)
-        algo = pick_algo(s);
+        algo = pick_algo(s, y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     switch (algo) {
         case DABNN_ALGO_REFERENCE: e = dabnn::launch_bconv_reference(a, w, y, s, st); break;
         case DABNN_ALGO_WREG: e = dabnn::launch_bconv_wreg(a, w, y, s, st); break;
-        case DABNN_ALGO_WLDS: e = dabnn::launch_bconv_wlds(a, w, y, s, st); break;
+        case DABNN_ALGO_AREG: e = dabnn::launch_bconv_areg(a, w, y, s, st); break;
         default: return DABNN_ERR_UNSUPPORTED;
     }
     if (e == hipErrorNotSupported)
@@ -145,7 +149,7 @@ int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int 
     dabnn::ConvShape s;
     if (make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad) != DABNN_OK)
         return -1;
-    return pick_algo(s);
+    return pick_algo(s, nullptr);
 }
 
 const char* dabnn_status_string(int status)

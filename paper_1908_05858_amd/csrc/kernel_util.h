@@ -1,0 +1,63 @@
+// Small device and host helpers shared by the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstdlib>
+#include <type_traits>
+
+namespace dabnn {
+
+// Compile-time loop: f(std::integral_constant<int, I>{}) for I in [I0, N).
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// Wait until every scalar load issued so far has landed (lgkmcnt = 0, other counters untouched).
+__device__ __forceinline__ void wait_scalar_loads()
+{
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+}
+
+// Nothing may be moved across this point by the instruction scheduler.
+__device__ __forceinline__ void schedule_fence()
+{
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+inline int env_int(const char* name, int fallback)
+{
+    const char* e = std::getenv(name);
+    return e ? std::atoi(e) : fallback;
+}
+
+inline int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0)
+            cus = 256;
+    }
+    return cus;
+}
+
+// Resident workgroups of 256 threads per CU for a kernel, queried once.
+template <class Kernel>
+inline int resident_blocks_per_cu(Kernel kernel)
+{
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb <= 0)
+        nb = 2;
+    return nb;
+}
+
+}  // namespace dabnn

@@ -22,9 +22,9 @@ hipError_t launch_bconv_reference(const uint64_t* a, const uint64_t* w, int32_t*
                                   const ConvShape& s, hipStream_t stream);
 hipError_t launch_bconv_wreg(const uint64_t* a, const uint64_t* w, int32_t* y,
                              const ConvShape& s, hipStream_t stream);
-hipError_t launch_bconv_wlds(const uint64_t* a, const uint64_t* w, int32_t* y,
+hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y,
                              const ConvShape& s, hipStream_t stream);
 bool bconv_wreg_supports(const ConvShape& s);
-bool bconv_wlds_supports(const ConvShape& s);
+bool bconv_areg_supports(const ConvShape& s, const void* y);
 
 }  // namespace dabnn

@@ -80,6 +80,6 @@ def test_bad_arguments_are_refused_before_any_launch(lib):
 
 
 def test_pick_algo(lib):
-    assert lib.dabnn_bconv2d_pick_algo(256, 56, 56, 64, 64, 3, 3, 1, 1) == 2
-    assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 5, 5, 1, 2) in (1, 3)
+    assert lib.dabnn_bconv2d_pick_algo(256, 56, 56, 64, 64, 3, 3, 1, 1) in (2, 3)
+    assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 5, 5, 1, 2) == 1
     assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 3, 3, 0, 1) == -1
