@@ -48,7 +48,7 @@ typedef enum {
                                  3x3 kernels with ceil(Cin/64) in {1,2,4,8}, stride 1 or 2 */
     DABNN_ALGO_AREG = 3       /* each lane keeps one output pixel's 3x3 window in VGPRs, weights are
                                  broadcast through SGPRs; 3x3 kernels with ceil(Cin/64) in
-                                 {1,2,4}, stride 1 or 2, Cout % 4 == 0, y 16-byte aligned */
+                                 {1,2,4,8}, stride 1 or 2, Cout % 4 == 0 (8 for Cin <= 64), y 16-byte aligned */
 } dabnn_algo;
 
 /* ceil(C / 64): 64-bit words per pixel for C channels.  Returns -1 if C <= 0. */

@@ -6,9 +6,15 @@
 // neighbouring pixels.  The wavefront then walks over output channels: the packed filter words
 // are the same for all 64 lanes, so they are fetched with scalar loads and used as the SGPR
 // operand of v_xor_b32, followed by v_bcnt_u32_b32 which accumulates the popcount (Eq. 6).  Four
-// output channels are computed together (four independent accumulation chains) and written as
-// one 16-byte store per lane.  All border handling happens once per window load; the hot loop
-// contains no address arithmetic, no masks and no LDS.
+// output channels are computed together (four independent accumulation chains).  All border
+// handling happens once per window load; the hot loop contains no address arithmetic, no masks
+// and no LDS.
+//
+// Stores: a lane holds consecutive channels of ONE pixel, so a direct store writes 16 bytes per
+// lane at a stride of Cout*4 bytes -- 64 partial cache lines per instruction, which saturates the
+// L2 write path long before HBM.  When Cout is a multiple of 16 the kernel therefore finishes 16
+// channels, transposes the 64x16 tile through a wavefront-private 4 KB slice of LDS and stores
+// it so that four neighbouring lanes write the 64 contiguous bytes of one pixel.
 //
 // This family suits layers with few words per pixel (small windows, small filters that stay in
 // the scalar cache); the filter-stationary family in bconv.hip suits the opposite case.
@@ -21,127 +27,130 @@ namespace {
 // acc[q] += sum_{d<3} popcount(w[q][d] ^ a[d]) for four output channels q.  w sits in SGPRs
 // (written by scalar loads only: a VALU-written SGPR would need wait states the compiler cannot
 // see inside the assembly), a in VGPRs.  Four independent chains hide the VALU latency.
+template <bool FIRST>
 __device__ __forceinline__ void xor_popc_4x3(int* acc, const uint32_t* a, const uint32_t* w0,
                                              const uint32_t* w1, const uint32_t* w2,
                                              const uint32_t* w3)
 {
     uint32_t t0, t1, t2, t3;
-    asm("v_xor_b32 %4, %11, %8\n\t"
-        "v_xor_b32 %5, %14, %8\n\t"
-        "v_xor_b32 %6, %17, %8\n\t"
-        "v_xor_b32 %7, %20, %8\n\t"
-        "v_bcnt_u32_b32 %0, %4, %0\n\t"
-        "v_bcnt_u32_b32 %1, %5, %1\n\t"
-        "v_bcnt_u32_b32 %2, %6, %2\n\t"
-        "v_bcnt_u32_b32 %3, %7, %3\n\t"
-        "v_xor_b32 %4, %12, %9\n\t"
-        "v_xor_b32 %5, %15, %9\n\t"
-        "v_xor_b32 %6, %18, %9\n\t"
-        "v_xor_b32 %7, %21, %9\n\t"
-        "v_bcnt_u32_b32 %0, %4, %0\n\t"
-        "v_bcnt_u32_b32 %1, %5, %1\n\t"
-        "v_bcnt_u32_b32 %2, %6, %2\n\t"
-        "v_bcnt_u32_b32 %3, %7, %3\n\t"
-        "v_xor_b32 %4, %13, %10\n\t"
-        "v_xor_b32 %5, %16, %10\n\t"
-        "v_xor_b32 %6, %19, %10\n\t"
-        "v_xor_b32 %7, %22, %10\n\t"
-        "v_bcnt_u32_b32 %0, %4, %0\n\t"
-        "v_bcnt_u32_b32 %1, %5, %1\n\t"
-        "v_bcnt_u32_b32 %2, %6, %2\n\t"
-        "v_bcnt_u32_b32 %3, %7, %3"
-        : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1), "=&v"(t2),
-          "=&v"(t3)
-        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "s"(w0[0]), "s"(w0[1]), "s"(w0[2]), "s"(w1[0]),
-          "s"(w1[1]), "s"(w1[2]), "s"(w2[0]), "s"(w2[1]), "s"(w2[2]), "s"(w3[0]), "s"(w3[1]),
-          "s"(w3[2]));
+#define DABNN_TAIL                                                                      \
+    "v_xor_b32 %4, %12, %9\n\t"                                                         \
+    "v_xor_b32 %5, %15, %9\n\t"                                                         \
+    "v_xor_b32 %6, %18, %9\n\t"                                                         \
+    "v_xor_b32 %7, %21, %9\n\t"                                                         \
+    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
+    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
+    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
+    "v_bcnt_u32_b32 %3, %7, %3\n\t"                                                     \
+    "v_xor_b32 %4, %13, %10\n\t"                                                        \
+    "v_xor_b32 %5, %16, %10\n\t"                                                        \
+    "v_xor_b32 %6, %19, %10\n\t"                                                        \
+    "v_xor_b32 %7, %22, %10\n\t"                                                        \
+    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
+    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
+    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
+    "v_bcnt_u32_b32 %3, %7, %3"
+#define DABNN_INPUTS                                                                          \
+    "v"(a[0]), "v"(a[1]), "v"(a[2]), "s"(w0[0]), "s"(w0[1]), "s"(w0[2]), "s"(w1[0]), "s"(w1[1]), \
+        "s"(w1[2]), "s"(w2[0]), "s"(w2[1]), "s"(w2[2]), "s"(w3[0]), "s"(w3[1]), "s"(w3[2])
+    if constexpr (FIRST) {
+        // the accumulators start here: the first popcounts add to the constant 0
+        asm("v_xor_b32 %4, %11, %8\n\t"
+            "v_xor_b32 %5, %14, %8\n\t"
+            "v_xor_b32 %6, %17, %8\n\t"
+            "v_xor_b32 %7, %20, %8\n\t"
+            "v_bcnt_u32_b32 %0, %4, 0\n\t"
+            "v_bcnt_u32_b32 %1, %5, 0\n\t"
+            "v_bcnt_u32_b32 %2, %6, 0\n\t"
+            "v_bcnt_u32_b32 %3, %7, 0\n\t" DABNN_TAIL
+            : "=&v"(acc[0]), "=&v"(acc[1]), "=&v"(acc[2]), "=&v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3)
+            : DABNN_INPUTS);
+    } else {
+        asm("v_xor_b32 %4, %11, %8\n\t"
+            "v_xor_b32 %5, %14, %8\n\t"
+            "v_xor_b32 %6, %17, %8\n\t"
+            "v_xor_b32 %7, %20, %8\n\t"
+            "v_bcnt_u32_b32 %0, %4, %0\n\t"
+            "v_bcnt_u32_b32 %1, %5, %1\n\t"
+            "v_bcnt_u32_b32 %2, %6, %2\n\t"
+            "v_bcnt_u32_b32 %3, %7, %3\n\t" DABNN_TAIL
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3)
+            : DABNN_INPUTS);
+    }
+#undef DABNN_TAIL
+#undef DABNN_INPUTS
 }
 
-// The same for two output channels and six dwords: operands %0-%1 accumulators, %2-%5
-// temporaries, %6-%11 activation dwords, %12-%17 / %18-%23 the two filters' dwords.
-#define DABNN_P2(A0, A1, W0A, W1A, W0B, W1B)                \
-    "v_xor_b32 %2, %" #W0A ", %" #A0 "\n\t"                 \
-    "v_xor_b32 %3, %" #W1A ", %" #A0 "\n\t"                 \
-    "v_xor_b32 %4, %" #W0B ", %" #A1 "\n\t"                 \
-    "v_xor_b32 %5, %" #W1B ", %" #A1 "\n\t"                 \
-    "v_bcnt_u32_b32 %0, %2, %0\n\t"                         \
-    "v_bcnt_u32_b32 %1, %3, %1\n\t"                         \
-    "v_bcnt_u32_b32 %0, %4, %0\n\t"                         \
-    "v_bcnt_u32_b32 %1, %5, %1\n\t"
-__device__ __forceinline__ void xor_popc_2x6(int* acc, const uint32_t* a, const uint32_t* w0,
-                                             const uint32_t* w1)
+// y = K - 2 * diff as one v_mad_i32_i24 (diff <= K < 2^23).  K is a kernel argument, so the SGPR
+// it sits in is written by a scalar load.
+__device__ __forceinline__ int finish_output(int diff, int K)
 {
-    uint32_t t0, t1, t2, t3;
-    asm(DABNN_P2(6, 7, 12, 18, 13, 19) DABNN_P2(8, 9, 14, 20, 15, 21) DABNN_P2(10, 11, 16, 22, 17, 23)
-        : "+v"(acc[0]), "+v"(acc[1]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
-        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "s"(w0[0]), "s"(w0[1]),
-          "s"(w0[2]), "s"(w0[3]), "s"(w0[4]), "s"(w0[5]), "s"(w1[0]), "s"(w1[1]), "s"(w1[2]),
-          "s"(w1[3]), "s"(w1[4]), "s"(w1[5]));
+    int y;
+    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(y) : "v"(diff), "s"(K));
+    return y;
 }
-#undef DABNN_P2
 
-// Geometry.  A group = CG output channels (the unit of work distribution and of the 16-byte
-// stores); it is consumed in software-pipeline units of NQ channels x DC dwords of K.
-//   V = 0: 4 channels x 6 dwords     V = 1: 2 channels x 18 dwords     V = 2: 4 channels x 9 dwords
-template <int CW, int V>
+// Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
+// and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
+// (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
+//   TR (transposed store through LDS): CG = 16.   Direct 16-byte stores: CG = 8 (Cw = 1) or 4.
+constexpr int kDC = 6;
+template <int CW, bool TR>
 struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
-    static constexpr int NQ = (V == 1) ? 2 : 4;
-    static constexpr int DC = (V == 0) ? 6 : (V == 1) ? 18 : 9;
-    static constexpr int CG = (V == 0 && CW == 1) ? 8 : 4;
-    static constexpr int CHUNKS = KD / DC;               // units per NQ channels
-    static constexpr int UNITS = (CG / NQ) * CHUNKS;     // units per group (always even)
-    static constexpr int SB = NQ * DC;                   // SGPRs per unit buffer
+    static constexpr int CG = TR ? 16 : (CW == 1 ? 8 : 4);
+    static constexpr int CHUNKS = KD / kDC;            // units per quad
+    static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
+    static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
 };
 
 // Scalar loads of unit UNIT of the group starting at output channel cout0.
-template <int CW, int V, int UNIT, int SB>
+template <int CW, bool TR, int UNIT, int SB>
 __device__ __forceinline__ void areg_load_unit(uint32_t (&sb)[SB], const uint32_t* __restrict__ w,
                                                int cout0)
 {
-    using G = AregGeom<CW, V>;
-    constexpr int sub = UNIT / G::CHUNKS;
+    using G = AregGeom<CW, TR>;
+    constexpr int quad = UNIT / G::CHUNKS;
     constexpr int chunk = UNIT % G::CHUNKS;
-    const uint32_t* src = w + static_cast<size_t>(cout0 + G::NQ * sub) * G::KD + chunk * G::DC;
+    const uint32_t* src = w + static_cast<size_t>(cout0 + 4 * quad) * G::KD + chunk * kDC;
 #pragma unroll
-    for (int q = 0; q < G::NQ; ++q) {
+    for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int d = 0; d < G::DC; ++d)
-            sb[q * G::DC + d] = src[q * G::KD + d];
+        for (int d = 0; d < kDC; ++d)
+            sb[q * kDC + d] = src[q * G::KD + d];
     }
 }
 
-template <int CW, int V, int UNIT, int SB, int KD, int CG>
+template <int CW, bool TR, int UNIT, int SB, int KD, int CG>
 __device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int (&acc)[CG],
                                                   const uint32_t (&areg)[KD])
 {
-    using G = AregGeom<CW, V>;
-    constexpr int sub = UNIT / G::CHUNKS;
+    using G = AregGeom<CW, TR>;
+    constexpr int quad = UNIT / G::CHUNKS;
     constexpr int chunk = UNIT % G::CHUNKS;
-    int* qa = &acc[G::NQ * sub];
-    const uint32_t* av = &areg[chunk * G::DC];
-    if constexpr (G::NQ == 4) {
-#pragma unroll
-        for (int h = 0; h < G::DC; h += 3)
-            xor_popc_4x3(qa, av + h, &sb[0 * G::DC + h], &sb[1 * G::DC + h], &sb[2 * G::DC + h],
-                         &sb[3 * G::DC + h]);
-    } else {
-#pragma unroll
-        for (int h = 0; h < G::DC; h += 6)
-            xor_popc_2x6(qa, av + h, &sb[0 * G::DC + h], &sb[1 * G::DC + h]);
-    }
+    // the quad's accumulators are born in its first block: no zero-initialisation needed
+    xor_popc_4x3<chunk == 0>(&acc[4 * quad], &areg[chunk * kDC], &sb[0 * kDC], &sb[1 * kDC],
+                             &sb[2 * kDC], &sb[3 * kDC]);
+    xor_popc_4x3<false>(&acc[4 * quad], &areg[chunk * kDC + 3], &sb[0 * kDC + 3], &sb[1 * kDC + 3],
+                        &sb[2 * kDC + 3], &sb[3 * kDC + 3]);
 }
 
-template <int CW, int S, int V>
+template <int CW, int S, bool TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
-    int n_ranges, int base_groups, int rem_groups, int dbg)
+    int n_ranges, int base_groups, int rem_groups)
 {
-    using G = AregGeom<CW, V>;
+    using G = AregGeom<CW, TR>;
+    // 64 pixels x 16 channels of int32 per wavefront, used only by the transposed store
+    __shared__ int32_t tile_lds[TR ? 4 * 64 * 16 : 4];
+
     const int lane = threadIdx.x & 63;
-    const int gw = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
     if (gw >= n_ranges)
         return;  // the grid is rounded up to whole workgroups
     // balanced contiguous partition of (tile, channel group) pairs, channel group fastest
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     load_window(tile);
 
     uint32_t sb0[G::SB], sb1[G::SB];
-    areg_load_unit<CW, V, 0>(sb0, w, cgi * G::CG);
+    areg_load_unit<CW, TR, 0>(sb0, w, cgi * G::CG);
 
     for (; g < g_end; ++g) {
         int ncgi = cgi + 1, ntile = tile;
@@ -209,43 +218,89 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         }
 
         int acc[G::CG];
-#pragma unroll
-        for (int q = 0; q < G::CG; ++q)
-            acc[q] = 0;
 
         // Software pipeline: while unit u feeds the VALU, unit u+1 is in flight.
         static_for<0, G::UNITS>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
             wait_scalar_loads();
             schedule_fence();
-            if (dbg & 2) {
-            } else if constexpr (u + 1 < G::UNITS) {
+            if constexpr (u + 1 < G::UNITS) {
                 if constexpr (u % 2 == 0)
-                    areg_load_unit<CW, V, u + 1>(sb1, w, cgi * G::CG);
+                    areg_load_unit<CW, TR, u + 1>(sb1, w, cgi * G::CG);
                 else
-                    areg_load_unit<CW, V, u + 1>(sb0, w, cgi * G::CG);
+                    areg_load_unit<CW, TR, u + 1>(sb0, w, cgi * G::CG);
             } else {
                 if (g + 1 < g_end)  // first unit of the next group (UNITS is even: buffer 0)
-                    areg_load_unit<CW, V, 0>(sb0, w, ncgi * G::CG);
+                    areg_load_unit<CW, TR, 0>(sb0, w, ncgi * G::CG);
             }
             schedule_fence();
             if constexpr (u % 2 == 0)
-                areg_compute_unit<CW, V, u>(sb0, acc, areg);
+                areg_compute_unit<CW, TR, u>(sb0, acc, areg);
             else
-                areg_compute_unit<CW, V, u>(sb1, acc, areg);
+                areg_compute_unit<CW, TR, u>(sb1, acc, areg);
             schedule_fence();
         });
 
-        if (pvalid && !((dbg & 1) && acc[0] != 12345)) {
-            int32_t* dst = y + ybase + static_cast<uint32_t>(cgi * G::CG);
+        if constexpr (TR) {
+            // Row P of the wavefront's LDS slice holds pixel P's 16 channels as four 16-byte
+            // quads; quad j sits in column j ^ ((P >> 1) & 3), which makes both the row-wise
+            // writes and the transposed reads free of bank conflicts.
+            int32_t* slice = tile_lds + wave * (64 * 16);
+            {
+                const int sw = (lane >> 1) & 3;
 #pragma unroll
-            for (int q = 0; q < G::CG; q += 4) {
-                int4 o;
-                o.x = __mul24(acc[q + 0], -2) + K;  // one v_mad_i32_i24; acc <= K < 2^23
-                o.y = __mul24(acc[q + 1], -2) + K;
-                o.z = __mul24(acc[q + 2], -2) + K;
-                o.w = __mul24(acc[q + 3], -2) + K;
-                *reinterpret_cast<int4*>(dst + q) = o;
+                for (int j = 0; j < 4; ++j) {
+                    int4 o;
+                    o.x = finish_output(acc[4 * j + 0], K);
+                    o.y = finish_output(acc[4 * j + 1], K);
+                    o.z = finish_output(acc[4 * j + 2], K);
+                    o.w = finish_output(acc[4 * j + 3], K);
+                    *reinterpret_cast<int4*>(slice + lane * 16 + 4 * (j ^ sw)) = o;
+                }
+            }
+            // LDS instructions of one wavefront execute in order; this only stops the compiler
+            // from moving the reads above the writes.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int j = lane & 3;
+            // uniform base + per-lane 32-bit byte offset
+            char* dst = reinterpret_cast<char*>(y + static_cast<size_t>(tile) * 64 * Cout + cgi * G::CG);
+            if (tile * 64 + 64 <= total_pix) {  // whole tile inside the tensor (uniform)
+                int4 o[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int P = 16 * k + (lane >> 2);  // four lanes per pixel: 64 contiguous bytes
+                    o[k] = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ ((P >> 1) & 3)));
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int P = 16 * k + (lane >> 2);
+                    *reinterpret_cast<int4*>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u) = o[k];
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int P = 16 * k + (lane >> 2);
+                    const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ ((P >> 1) & 3)));
+                    if (tile * 64 + P < total_pix)
+                        *reinterpret_cast<int4*>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u) = o;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            if (pvalid) {
+                int32_t* dst = y + ybase + static_cast<uint32_t>(cgi * G::CG);
+#pragma unroll
+                for (int q = 0; q < G::CG; q += 4) {
+                    int4 o;
+                    o.x = finish_output(acc[q + 0], K);
+                    o.y = finish_output(acc[q + 1], K);
+                    o.z = finish_output(acc[q + 2], K);
+                    o.w = finish_output(acc[q + 3], K);
+                    *reinterpret_cast<int4*>(dst + q) = o;
+                }
             }
         }
 
@@ -256,13 +311,13 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     }
 }
 
-template <int CW, int S, int V>
+template <int CW, int S, bool TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream)
 {
-    using G = AregGeom<CW, V>;
-    static_assert(G::UNITS % 2 == 0 && G::KD % G::DC == 0 && G::CG % G::NQ == 0, "pipeline geometry");
-    auto kernel = bconv3x3_areg_kernel<CW, S, V>;
+    using G = AregGeom<CW, TR>;
+    static_assert(G::UNITS % 2 == 0 && G::KD % kDC == 0, "pipeline geometry");
+    auto kernel = bconv3x3_areg_kernel<CW, S, TR>;
     static const int blocks_per_cu = resident_blocks_per_cu(kernel);
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 63) / 64;
@@ -283,7 +338,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
                        s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
-                       rem_groups, env_int("DABNN_DBG", 0));
+                       rem_groups);
     return hipGetLastError();
 }
 
@@ -291,15 +346,12 @@ template <int CW>
 hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                          hipStream_t stream)
 {
-    const int v = env_int("DABNN_AREG_V", 0);
-    if (s.stride == 1) {
-        if (v == 1) return launch_areg_inst<CW, 1, 1>(a, w, y, s, stream);
-        if (v == 2) return launch_areg_inst<CW, 1, 2>(a, w, y, s, stream);
-        return launch_areg_inst<CW, 1, 0>(a, w, y, s, stream);
-    }
-    if (v == 1) return launch_areg_inst<CW, 2, 1>(a, w, y, s, stream);
-    if (v == 2) return launch_areg_inst<CW, 2, 2>(a, w, y, s, stream);
-    return launch_areg_inst<CW, 2, 0>(a, w, y, s, stream);
+    const bool tr = (s.Cout % 16 == 0) && env_int("DABNN_AREG_DIRECT", 0) == 0;
+    if (s.stride == 1)
+        return tr ? launch_areg_inst<CW, 1, true>(a, w, y, s, stream)
+                  : launch_areg_inst<CW, 1, false>(a, w, y, s, stream);
+    return tr ? launch_areg_inst<CW, 2, true>(a, w, y, s, stream)
+              : launch_areg_inst<CW, 2, false>(a, w, y, s, stream);
 }
 
 }  // namespace
@@ -308,7 +360,7 @@ bool bconv_areg_supports(const ConvShape& s, const void* y)
 {
     if (!(s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2)))
         return false;
-    if (!(s.Cw == 1 || s.Cw == 2 || s.Cw == 4))
+    if (!(s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8))
         return false;
     const int cg = (s.Cw == 1) ? 8 : 4;
     return s.Cout % cg == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
@@ -324,7 +376,8 @@ hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, c
     switch (s.Cw) {
         case 1: return launch_areg_s<1>(a32, w32, y, s, stream);
         case 2: return launch_areg_s<2>(a32, w32, y, s, stream);
-        default: return launch_areg_s<4>(a32, w32, y, s, stream);
+        case 4: return launch_areg_s<4>(a32, w32, y, s, stream);
+        default: return launch_areg_s<8>(a32, w32, y, s, stream);
     }
 }
 
