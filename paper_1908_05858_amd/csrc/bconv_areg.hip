@@ -92,6 +92,15 @@ __device__ __forceinline__ int finish_output(int diff, int K)
     return y;
 }
 
+// Outputs are written once and never read by this kernel: store them non-temporally so that they
+// stream through L2 instead of piling up as dirty lines that the end of the kernel must flush.
+typedef int v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_out4(void* dst, const int4& o)
+{
+    v4i v = {o.x, o.y, o.z, o.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
+}
+
 // Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
 // and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
 // (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
@@ -276,7 +285,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int P = 16 * k + (lane >> 2);
-                    *reinterpret_cast<int4*>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u) = o[k];
+                    store_out4(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o[k]);
                 }
             } else {
 #pragma unroll
@@ -284,7 +293,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     const int P = 16 * k + (lane >> 2);
                     const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ ((P >> 1) & 3)));
                     if (tile * 64 + P < total_pix)
-                        *reinterpret_cast<int4*>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u) = o;
+                        store_out4(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o);
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     o.y = finish_output(acc[q + 1], K);
                     o.z = finish_output(acc[q + 2], K);
                     o.w = finish_output(acc[q + 3], K);
-                    *reinterpret_cast<int4*>(dst + q) = o;
+                    store_out4(dst + q, o);
                 }
             }
         }
@@ -346,7 +355,9 @@ template <int CW>
 hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                          hipStream_t stream)
 {
-    const bool tr = (s.Cout % 16 == 0) && env_int("DABNN_AREG_DIRECT", 0) == 0;
+    // The transposed store pays off while the output write rate per VALU cycle is high; with 8
+    // words per pixel (K = 4608) the direct store is cheaper than the trip through LDS.
+    const bool tr = (s.Cout % 16 == 0) && CW <= 4;
     if (s.stride == 1)
         return tr ? launch_areg_inst<CW, 1, true>(a, w, y, s, stream)
                   : launch_areg_inst<CW, 1, false>(a, w, y, s, stream);

@@ -46,14 +46,12 @@ int make_shape(dabnn::ConvShape& s, int N, int H, int W, int Cin, int Cout, int 
 
 int pick_algo(const dabnn::ConvShape& s, const void* y)
 {
-    // Keep the larger operand in VGPRs and stream the smaller one through the scalar path:
-    // few words per pixel -> activation window stationary; many -> filter stationary.
-    if (s.Cw <= 2 && dabnn::bconv_areg_supports(s, y))
+    // Measured on MI355X at the Bi-Real-18 shapes, the activation-stationary family is the
+    // faster one wherever it applies; the filter-stationary family covers Cout % 4 != 0.
+    if (dabnn::bconv_areg_supports(s, y))
         return DABNN_ALGO_AREG;
     if (dabnn::bconv_wreg_supports(s))
         return DABNN_ALGO_WREG;
-    if (dabnn::bconv_areg_supports(s, y))
-        return DABNN_ALGO_AREG;
     return DABNN_ALGO_REFERENCE;
 }
 
