@@ -31,6 +31,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=None, help="override the batch (default 256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device tensor copy (a kernel of known "
+                         "HBM traffic) so that counter runs under rocprofv3 --pmc can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; batch sharding across GPUs is a design note "
@@ -72,6 +75,13 @@ def main():
             binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li])
             if li == probe:
                 events[2].record()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

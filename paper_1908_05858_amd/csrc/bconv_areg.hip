@@ -13,8 +13,8 @@
 // Stores: a lane holds consecutive channels of ONE pixel, so a direct store writes 16 bytes per
 // lane at a stride of Cout*4 bytes -- 64 partial cache lines per instruction, which saturates the
 // L2 write path long before HBM.  When Cout is a multiple of 16 the kernel therefore finishes 16
-// channels, transposes the 64x16 tile through a wavefront-private 4 KB slice of LDS and stores
-// it so that four neighbouring lanes write the 64 contiguous bytes of one pixel.
+// (or 32) channels, transposes the 64 x 16 tile through a wavefront-private slice of LDS and
+// stores it so that neighbouring lanes write the 64 (or 128) contiguous bytes of one pixel.
 //
 // This family suits layers with few words per pixel (small windows, small filters that stay in
 // the scalar cache); the filter-stationary family in bconv.hip suits the opposite case.
@@ -92,32 +92,38 @@ __device__ __forceinline__ int finish_output(int diff, int K)
     return y;
 }
 
-// Outputs are written once and never read by this kernel: store them non-temporally so that they
-// stream through L2 instead of piling up as dirty lines that the end of the kernel must flush.
+// Outputs are written once and never read by this kernel.  The transposed path stores whole
+// 64- or 128-byte runs, so it stores non-temporally (streaming through L2); the direct path
+// writes 16-byte pieces of a line at different times and leaves it to L2 to merge them.
 typedef int v4i __attribute__((ext_vector_type(4)));
+template <bool STREAM>
 __device__ __forceinline__ void store_out4(void* dst, const int4& o)
 {
     v4i v = {o.x, o.y, o.z, o.w};
-    __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
+    if constexpr (STREAM)
+        __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
+    else
+        *reinterpret_cast<v4i*>(dst) = v;
 }
 
 // Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
 // and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
 // (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
-//   TR (transposed store through LDS): CG = 16.   Direct 16-byte stores: CG = 8 (Cw = 1) or 4.
+//   TR = 16 or 32 (transposed store through LDS): CG = TR.   TR = 0, direct 16-byte stores:
+//   CG = 8 (Cw = 1) or 4.
 constexpr int kDC = 6;
-template <int CW, bool TR>
+template <int CW, int TR>
 struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
-    static constexpr int CG = TR ? 16 : (CW == 1 ? 8 : 4);
+    static constexpr int CG = TR ? TR : (CW == 1 ? 8 : 4);
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
 };
 
 // Scalar loads of unit UNIT of the group starting at output channel cout0.
-template <int CW, bool TR, int UNIT, int SB>
+template <int CW, int TR, int UNIT, int SB>
 __device__ __forceinline__ void areg_load_unit(uint32_t (&sb)[SB], const uint32_t* __restrict__ w,
                                                int cout0)
 {
@@ -133,7 +139,7 @@ __device__ __forceinline__ void areg_load_unit(uint32_t (&sb)[SB], const uint32_
     }
 }
 
-template <int CW, bool TR, int UNIT, int SB, int KD, int CG>
+template <int CW, int TR, int UNIT, int SB, int KD, int CG>
 __device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int (&acc)[CG],
                                                   const uint32_t (&areg)[KD])
 {
@@ -147,7 +153,7 @@ __device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int 
                         &sb[2 * kDC + 3], &sb[3 * kDC + 3]);
 }
 
-template <int CW, int S, bool TR>
+template <int CW, int S, int TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
@@ -155,7 +161,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 {
     using G = AregGeom<CW, TR>;
     // 64 pixels x 16 channels of int32 per wavefront, used only by the transposed store
-    __shared__ int32_t tile_lds[TR ? 4 * 64 * 16 : 4];
+    __shared__ int32_t tile_lds[TR ? 4 * 64 * TR : 4];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -250,21 +256,26 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             schedule_fence();
         });
 
-        if constexpr (TR) {
-            // Row P of the wavefront's LDS slice holds pixel P's 16 channels as four 16-byte
-            // quads; quad j sits in column j ^ ((P >> 1) & 3), which makes both the row-wise
-            // writes and the transposed reads free of bank conflicts.
-            int32_t* slice = tile_lds + wave * (64 * 16);
+        if constexpr (TR != 0) {
+            // Row P of the wavefront's LDS slice holds pixel P's TR channels as QPR 16-byte quads.
+            // Quad j sits in column j ^ swz(P), which makes both the row-wise writes and the
+            // transposed reads free of bank conflicts (a 64-byte row covers half the banks, so
+            // two neighbouring rows share one swizzle; a 128-byte row covers all of them).
+            constexpr int QPR = TR / 4;            // quads per row
+            constexpr int LPP = QPR;               // lanes per pixel in the transposed store
+            constexpr int PPI = 64 / LPP;          // pixels per store instruction
+            auto swz = [](int P) { return (TR == 16) ? ((P >> 1) & 3) : (P & 7); };
+            int32_t* slice = tile_lds + wave * (64 * TR);
             {
-                const int sw = (lane >> 1) & 3;
+                const int sw = swz(lane);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < QPR; ++j) {
                     int4 o;
                     o.x = finish_output(acc[4 * j + 0], K);
                     o.y = finish_output(acc[4 * j + 1], K);
                     o.z = finish_output(acc[4 * j + 2], K);
                     o.w = finish_output(acc[4 * j + 3], K);
-                    *reinterpret_cast<int4*>(slice + lane * 16 + 4 * (j ^ sw)) = o;
+                    *reinterpret_cast<int4*>(slice + lane * TR + 4 * (j ^ sw)) = o;
                 }
             }
             // LDS instructions of one wavefront execute in order; this only stops the compiler
@@ -272,28 +283,29 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int j = lane & 3;
-            // uniform base + per-lane 32-bit byte offset
+            const int j = lane % LPP;
+            // uniform base + per-lane 32-bit byte offset; LPP neighbouring lanes write the
+            // 4*TR contiguous bytes of one pixel
             char* dst = reinterpret_cast<char*>(y + static_cast<size_t>(tile) * 64 * Cout + cgi * G::CG);
             if (tile * 64 + 64 <= total_pix) {  // whole tile inside the tensor (uniform)
-                int4 o[4];
+                int4 o[LPP];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int P = 16 * k + (lane >> 2);  // four lanes per pixel: 64 contiguous bytes
-                    o[k] = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ ((P >> 1) & 3)));
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    o[k] = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
                 }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int P = 16 * k + (lane >> 2);
-                    store_out4(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o[k]);
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    store_out4<true>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o[k]);
                 }
             } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int P = 16 * k + (lane >> 2);
-                    const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ ((P >> 1) & 3)));
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    const int4 o = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
                     if (tile * 64 + P < total_pix)
-                        store_out4(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o);
+                        store_out4<true>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o);
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -308,7 +320,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     o.y = finish_output(acc[q + 1], K);
                     o.z = finish_output(acc[q + 2], K);
                     o.w = finish_output(acc[q + 3], K);
-                    store_out4(dst + q, o);
+                    store_out4<false>(dst + q, o);
                 }
             }
         }
@@ -320,7 +332,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     }
 }
 
-template <int CW, int S, bool TR>
+template <int CW, int S, int TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream)
 {
@@ -357,12 +369,22 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
 {
     // The transposed store pays off while the output write rate per VALU cycle is high; with 8
     // words per pixel (K = 4608) the direct store is cheaper than the trip through LDS.
-    const bool tr = (s.Cout % 16 == 0) && CW <= 4;
-    if (s.stride == 1)
-        return tr ? launch_areg_inst<CW, 1, true>(a, w, y, s, stream)
-                  : launch_areg_inst<CW, 1, false>(a, w, y, s, stream);
-    return tr ? launch_areg_inst<CW, 2, true>(a, w, y, s, stream)
-              : launch_areg_inst<CW, 2, false>(a, w, y, s, stream);
+    // Transposing 32 channels writes whole 128-byte lines (HBM write traffic equals the
+    // algorithmic bytes) but costs registers and LDS; 16 channels (64-byte runs, 8-18 % extra
+    // write traffic) is the faster choice at the Bi-Real-18 shapes.  With 8 words per pixel
+    // (K = 4608) the output rate is so low that the direct store wins.
+    int tr = (CW <= 4 && s.Cout % 16 == 0) ? 16 : 0;
+    const int forced = env_int("DABNN_AREG_TR", -1);
+    if (forced == 0 || (forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
+        tr = forced;
+    if (s.stride == 1) {
+        if (tr == 32) return launch_areg_inst<CW, 1, 32>(a, w, y, s, stream);
+        if (tr == 16) return launch_areg_inst<CW, 1, 16>(a, w, y, s, stream);
+        return launch_areg_inst<CW, 1, 0>(a, w, y, s, stream);
+    }
+    if (tr == 32) return launch_areg_inst<CW, 2, 32>(a, w, y, s, stream);
+    if (tr == 16) return launch_areg_inst<CW, 2, 16>(a, w, y, s, stream);
+    return launch_areg_inst<CW, 2, 0>(a, w, y, s, stream);
 }
 
 }  // namespace
