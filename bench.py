@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 # 2 lane-ops => 32 ops per lane-op => 1258.29 TOP/s.
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 * 32 / 1e12
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per step (16 launches) at batch 256, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE) scaled by a plain 1 GiB copy; see profiles/bench_bireal18_b256_hbm_traffic.md.
+# Algorithmic: conv 1.597e9 (56 MB read + 1541 MB written), bit-pack 1.775e9.
+MEASURED_TRAFFIC_B256 = {"bconv": 1.937e9, "bitpack": 1.776e9}
 
 
 def main():
@@ -170,7 +174,8 @@ def main():
             "peak": round(VALU_PEAK_TOPS, 2),
             "unit": "TOP/s",
             "frac": round(conv_tops / VALU_PEAK_TOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_B256["bconv"] if N == 256 else None,
+            "traffic_note": "HBM bytes per step over the 16 conv launches (algorithmic 1.597e9)",
         },
         "roofline_bitpack": {
             "kernel": "bitpack (all 16 launches of dabnn_bitpack in a step)",
@@ -179,7 +184,8 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(pack_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_B256["bitpack"] if N == 256 else None,
+            "traffic_note": "HBM bytes per step over the 16 bit-pack launches (algorithmic 1.775e9)",
         },
         "per_layer": per_layer,
     }

@@ -304,8 +304,7 @@ hipError_t launch_wreg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const int groups = (s.Cout + 63) / 64;
     // Resident wavefront slots, split between channel groups; every range gets the same number
     // of tasks (+-1), so all wavefronts finish together in a single resident round.
-    const int oversub = env_int("DABNN_WREG_OVERSUB", 1);
-    const int64_t slots = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4 * oversub;
+    const int64_t slots = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
     int ranges = static_cast<int>(slots / groups);
     if (ranges < 1)
         ranges = 1;
@@ -328,7 +327,7 @@ hipError_t launch_wreg_p(const uint32_t* a, const uint32_t* w, int32_t* y, const
     const int waste8 = (s.Wo + 7) / 8 * 8 - s.Wo;
     const int waste7 = (s.Wo + 6) / 7 * 7 - s.Wo;
     int p = (waste7 < waste8) ? 7 : 8;
-    const int forced = env_int("DABNN_WREG_P", 0);
+    const int forced = env_int("DABNN_WREG_P", 0);  // test hook: force the chunk width
     if (forced == 7 || forced == 8)
         p = forced;
     if (p == 7)

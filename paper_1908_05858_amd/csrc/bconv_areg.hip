@@ -349,8 +349,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const int n_groups = static_cast<int>(n_groups64);
     // Exactly the resident wavefront slots; every wavefront gets the same number of groups
     // (+-1), so the launch is one balanced round.
-    const int oversub = env_int("DABNN_AREG_OVERSUB", 1);
-    int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4 * oversub;
+    int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
     if (ranges > n_groups)
         ranges = n_groups;
     const int n_ranges = static_cast<int>(ranges);
@@ -374,7 +373,7 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     // write traffic) is the faster choice at the Bi-Real-18 shapes.  With 8 words per pixel
     // (K = 4608) the output rate is so low that the direct store wins.
     int tr = (CW <= 4 && s.Cout % 16 == 0) ? 16 : 0;
-    const int forced = env_int("DABNN_AREG_TR", -1);
+    const int forced = env_int("DABNN_AREG_TR", -1);  // test hook: force the store variant
     if (forced == 0 || (forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
         tr = forced;
     if (s.stride == 1) {

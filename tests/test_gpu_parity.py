@@ -169,6 +169,20 @@ def test_odd_shapes_tuned(dabnn, oracle, shape, algo):
     run_conv(dabnn, oracle, *shape, seed=999 + sum(shape), algo=algo)
 
 
+@pytest.mark.parametrize("env", [("DABNN_AREG_TR", "0", 3), ("DABNN_AREG_TR", "16", 3), ("DABNN_AREG_TR", "32", 3),
+                                 ("DABNN_WREG_P", "7", 2), ("DABNN_WREG_P", "8", 2)],
+                         ids=lambda e: f"{e[0]}={e[1]}")
+def test_kernel_variants(dabnn, oracle, env, monkeypatch):
+    """Every store variant of the activation-stationary family and both chunk widths of the
+    filter-stationary family, forced through the library's test hooks."""
+    name, value, algo = env
+    monkeypatch.setenv(name, value)
+    for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
+                  (2, 7, 7, 512, 64, 3, 1, 1), (1, 57, 30, 64, 32, 3, 1, 1)]:
+        print("variant", env, shape, flush=True)
+        run_conv(dabnn, oracle, *shape, seed=31337 + sum(shape), algo=algo)
+
+
 def test_closed_forms_on_gpu(dabnn):
     """All-equal gives +K, all-opposite gives -K, with the border taps counted as +1."""
     for (N, H, W, Cin, Cout, k, s, p) in [(2, 14, 14, 64, 64, 3, 1, 1), (1, 9, 9, 80, 70, 3, 2, 1)]:
