@@ -98,6 +98,36 @@ int dabnn_bconv2d_algo(const uint64_t *a, const uint64_t *w, int32_t *y, int N, 
                        int Cin, int Cout, int kh, int kw, int stride, int pad, int algo,
                        void *stream);
 
+/*
+ * Binary convolution fused with batch-norm and binarization: the output is the NEXT layer's packed
+ * activation tensor, so neither the int32 feature map nor a separate bit-pack pass exists.  The
+ * paper notes that its packing is compatible with a fused BN-binarization layer (Sec. 2.1.1, last
+ * sentence); the layer computed here is sign(BN(conv)), expressed on the integer conv output y:
+ *
+ *   bit(n,ho,wo,co) = (y[n,ho,wo,co] < thr[co]) XOR flip bit co          (bit 1 <-> -1)
+ *
+ *   a, w  : as for dabnn_bconv2d
+ *   thr   : i32 [Cout]            device, every value within [-2^30, 2^30]
+ *   flip  : u64 [ceil(Cout/64)]   device, bit co%64 of word co/64, tail bits 0
+ *   out   : u64 [N][Ho][Wo][ceil(Cout/64)]  device, written completely, tail bits 0
+ * dabnn_bn_thresholds derives thr and flip from batch-norm parameters.
+ */
+int dabnn_bconv2d_bnsign(const uint64_t *a, const uint64_t *w, const int32_t *thr,
+                         const uint64_t *flip, uint64_t *out, int N, int H, int W, int Cin,
+                         int Cout, int kh, int kw, int stride, int pad, void *stream);
+
+/*
+ * HOST helper (every pointer is a HOST pointer; nothing is launched): integer thresholds that
+ * reproduce, for every integer y in [-K, K], the sign of the inference-time batch-norm evaluated
+ * in fp64,   z = gamma[c] * (y - mean[c]) / sqrt(var[c] + eps) + beta[c],   bit = 1 iff z < 0:
+ *   (y < thr[c]) XOR flip bit c  ==  (z < 0).
+ * gamma > 0 gives flip 0, gamma < 0 flip 1; gamma == 0 (or a NaN anywhere) gives a constant bit.
+ *   gamma, beta, mean, var : f32 [Cout];  thr : i32 [Cout];  flip : u64 [ceil(Cout/64)]
+ * Returns DABNN_ERR_NULL / DABNN_ERR_SHAPE (Cout <= 0, K <= 0 or K >= 2^30) like the other calls.
+ */
+int dabnn_bn_thresholds(const float *gamma, const float *beta, const float *mean, const float *var,
+                        float eps, int Cout, int K, int32_t *thr, uint64_t *flip);
+
 /* Which dabnn_algo DABNN_ALGO_AUTO resolves to for this shape with a 16-byte aligned y (no
  * launch); -1 if the shape is invalid. */
 int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,

@@ -6,7 +6,8 @@ package.  It imports nothing from the GPU package and the GPU package imports no
 
 What each function computes, with the passage it follows, is stated in ``dabnn_oracle.c``:
 ``sign`` / ``bitpack`` follow Sec. 2.1.1; ``bconv2d`` is the +-1 float cross-correlation that
-Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal; ``glue`` only generates inputs.
+Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal; ``bconv2d_bnsign`` is that convolution followed by
+fp64 batch-norm and the sign (fused BN-binarization, Sec. 2.1.1); ``glue`` only generates inputs.
 
 Every function here is pinned by ``tests/test_oracle_pins.py`` (closed forms, invariants, brute
 force, torch's CPU conv2d, numpy.packbits); none is "parity unpinned".
@@ -49,8 +50,9 @@ def _load():
     lib.oracle_bconv2d.argtypes = [vp, vp, vp] + [i32] * 9
     lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
     lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
+    lib.oracle_bconv2d_bnsign.argtypes = [vp] * 6 + [ctypes.c_float, vp] + [i32] * 9
     for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
-              lib.oracle_bconv2d_at, lib.oracle_glue):
+              lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign):
         f.restype = i32
     _lib = lib
     return lib
@@ -122,6 +124,26 @@ def bconv2d_at(A, Wt, idx, stride=1, pad=0):
     _check(_load().oracle_bconv2d_at(A.ctypes.data, Wt.ctypes.data, idx.ctypes.data, idx.shape[0],
                                      out.ctypes.data, N, H, W, Cin, Cout, kh, kw, stride, pad),
            "bconv2d_at")
+    return out
+
+
+def bconv2d_bnsign(x, w, gamma, beta, mean, var, eps, stride=1, pad=0, sign_rule=SIGN_BIT):
+    """sign(BN(bconv2d(x, w))) packed into words: uint64 [N,Ho,Wo,ceil(Cout/64)] (Sec. 2.1.1,
+    fused BN-binarization; BN in fp64, bit = 1 iff z < 0)."""
+    A, Wt = sign(x, sign_rule), sign(w, sign_rule)
+    gamma, beta, mean, var = _f32(gamma), _f32(beta), _f32(mean), _f32(var)
+    N, H, W, Cin = A.shape
+    Cout, kh, kw, Cin2 = Wt.shape
+    if Cin != Cin2 or any(v.shape != (Cout,) for v in (gamma, beta, mean, var)):
+        raise ValueError("shape mismatch")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    out = np.empty((N, Ho, Wo, (Cout + 63) // 64), dtype=np.uint64)
+    _check(_load().oracle_bconv2d_bnsign(A.ctypes.data, Wt.ctypes.data, gamma.ctypes.data,
+                                         beta.ctypes.data, mean.ctypes.data, var.ctypes.data,
+                                         ctypes.c_float(eps), out.ctypes.data, N, H, W, Cin, Cout, kh,
+                                         kw, stride, pad), "bconv2d_bnsign")
     return out
 
 

@@ -173,6 +173,50 @@ int oracle_bconv2d_at(const float *A, const float *Wt, const int32_t *idx, int64
 }
 
 /*
+ * Binary convolution fused with batch-norm and binarization (Sec. 2.1.1, last sentence: the
+ * packing scheme is compatible with a fused BN-binarization layer).  Reading taken: the layer is
+ * sign(BN(conv)), with inference-time batch-norm per output channel evaluated in fp64,
+ *
+ *   z = gamma[co] * (y - mean[co]) / sqrt(var[co] + eps) + beta[co],     bit = 1 iff z < 0,
+ *
+ * where y is the integer convolution output above; z == 0 counts as +1 (bit 0).  The bits of a
+ * pixel are packed like every other tensor here: channel co -> word co/64, bit co%64, tail 0.
+ *   out : [N][Ho][Wo][ceil(Cout/64)] words
+ */
+int oracle_bconv2d_bnsign(const float *A, const float *Wt, const float *gamma, const float *beta,
+                          const float *mean, const float *var, float eps, uint64_t *out, int N,
+                          int H, int W, int Cin, int Cout, int kh, int kw, int stride, int pad)
+{
+    if (!A || !Wt || !gamma || !beta || !mean || !var || !out || N <= 0 || Cin <= 0 || Cout <= 0)
+        return ORACLE_BAD_ARG;
+    const int Ho = out_dim(H, kh, stride, pad);
+    const int Wo = out_dim(W, kw, stride, pad);
+    if (Ho <= 0 || Wo <= 0 || (int64_t)kh * kw * Cin >= ((int64_t)1 << 24))
+        return ORACLE_BAD_ARG;
+    const int words = (Cout + 63) / 64;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int ho = 0; ho < Ho; ++ho) {
+            for (int wo = 0; wo < Wo; ++wo) {
+                uint64_t *row = out + (((int64_t)n * Ho + ho) * Wo + wo) * words;
+                for (int j = 0; j < words; ++j)
+                    row[j] = 0;
+                for (int co = 0; co < Cout; ++co) {
+                    const int32_t yv =
+                        conv_one(A, Wt, n, ho, wo, co, H, W, Cin, kh, kw, stride, pad);
+                    const double z = (double)gamma[co] * ((double)yv - (double)mean[co]) /
+                                         sqrt((double)var[co] + (double)eps) +
+                                     (double)beta[co];
+                    if (z < 0.0)
+                        row[co / 64] |= (uint64_t)1 << (co % 64);
+                }
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Stand-in for the float glue between two binary convolutions of a Bi-Real-Net-18 body
  * (batch-norm plus shortcut), used only to GENERATE the next layer's fp32 input for the
  * full-network workload.  It is not part of the method under test; the GPU never computes it.

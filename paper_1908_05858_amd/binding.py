@@ -41,12 +41,16 @@ def load():
     lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
+    lib.dabnn_bconv2d_bnsign.argtypes, lib.dabnn_bconv2d_bnsign.restype = [vp] * 5 + [i32] * 9 + [vp], i32
+    lib.dabnn_bn_thresholds.argtypes = [vp] * 4 + [ctypes.c_float, i32, i32, vp, vp]
+    lib.dabnn_bn_thresholds.restype = i32
     _lib = lib
     return lib
 
 
 EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
-           "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string"]
+           "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
+           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds"]
 
 
 def status_string(status):
@@ -123,3 +127,40 @@ def bconv2d(a, w, Cin, stride=1, pad=0, out=None, algo=ALGO_AUTO):
 
 def pick_algo(N, H, W, Cin, Cout, kh, kw, stride, pad):
     return load().dabnn_bconv2d_pick_algo(N, H, W, Cin, Cout, kh, kw, stride, pad)
+
+
+def bn_thresholds(gamma, beta, mean, var, eps, K, device="cuda"):
+    """Batch-norm parameters (host float32 arrays of length Cout) -> (thr int32 [Cout], flip
+    int64 [ceil(Cout/64)]) on `device`, computed by the library's host helper."""
+    import numpy as np
+    arrs = [np.ascontiguousarray(v, dtype=np.float32) for v in (gamma, beta, mean, var)]
+    Cout = arrs[0].shape[0]
+    if any(v.shape != (Cout,) for v in arrs):
+        raise ValueError("batch-norm parameters must all have shape (Cout,)")
+    thr = np.empty(Cout, dtype=np.int32)
+    flip = np.empty((Cout + 63) // 64, dtype=np.int64)
+    _check(load().dabnn_bn_thresholds(*[ctypes.c_void_p(v.ctypes.data) for v in arrs], ctypes.c_float(eps),
+                                      Cout, K, ctypes.c_void_p(thr.ctypes.data),
+                                      ctypes.c_void_p(flip.ctypes.data)), "dabnn_bn_thresholds")
+    return torch.from_numpy(thr).to(device), torch.from_numpy(flip).to(device)
+
+
+def bconv2d_bnsign(a, w, thr, flip, Cin, stride=1, pad=0, out=None):
+    """Fused conv + threshold + bit-pack: packed a, w -> int64 [N,Ho,Wo,ceil(Cout/64)] (the next
+    layer's packed activations)."""
+    N, H, W, Cw = a.shape
+    Cout, kh, kw, Cw2 = w.shape
+    if Cw != Cw2 or Cw != (Cin + 63) // 64:
+        raise ValueError("packed word counts do not match Cin")
+    if thr.shape != (Cout,) or flip.shape != ((Cout + 63) // 64,):
+        raise ValueError("thr / flip do not match Cout")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_bnsign")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, (Cout + 63) // 64), dtype=torch.int64, device=a.device)
+    _check(load().dabnn_bconv2d_bnsign(_dev(a, torch.int64, "a"), _dev(w, torch.int64, "w"),
+                                       _dev(thr, torch.int32, "thr"), _dev(flip, torch.int64, "flip"),
+                                       _dev(out, torch.int64, "out"), N, H, W, Cin, Cout, kh, kw, stride,
+                                       pad, _stream()), "dabnn_bconv2d_bnsign")
+    return out

@@ -59,6 +59,45 @@ __global__ __launch_bounds__(256) void bconv_reference_kernel(
     y[idx] = s.K - 2 * diff;
 }
 
+// One thread per (pixel, 64-channel output word) of the fused conv + threshold + bit-pack.
+__global__ __launch_bounds__(256) void bconv_bnsign_reference_kernel(
+    const uint64_t* __restrict__ a, const uint64_t* __restrict__ w,
+    const int32_t* __restrict__ thr, const uint64_t* __restrict__ flip, uint64_t* __restrict__ out,
+    ConvShape s, int64_t total)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= total)
+        return;
+    const int words = (s.Cout + 63) / 64;
+    const int word = static_cast<int>(idx % words);
+    int64_t pix = idx / words;
+    const int wo = static_cast<int>(pix % s.Wo);
+    pix /= s.Wo;
+    const int ho = static_cast<int>(pix % s.Ho);
+    const int n = static_cast<int>(pix / s.Ho);
+    uint64_t bits = 0;
+    for (int c = 0; c < 64 && word * 64 + c < s.Cout; ++c) {
+        const int co = word * 64 + c;
+        int diff = 0;
+        for (int i = 0; i < s.kh; ++i) {
+            const int hi = ho * s.stride - s.pad + i;
+            for (int j = 0; j < s.kw; ++j) {
+                const int wi = wo * s.stride - s.pad + j;
+                const uint64_t* wp = w + ((static_cast<int64_t>(co) * s.kh + i) * s.kw + j) * s.Cw;
+                const bool inside = hi >= 0 && hi < s.H && wi >= 0 && wi < s.W;
+                const uint64_t* ap = a + ((static_cast<int64_t>(n) * s.H + (inside ? hi : 0)) * s.W +
+                                          (inside ? wi : 0)) * s.Cw;
+                for (int q = 0; q < s.Cw; ++q)
+                    diff += __popcll((inside ? ap[q] : 0ull) ^ wp[q]);
+            }
+        }
+        const int yv = s.K - 2 * diff;
+        if (yv < thr[co])
+            bits |= 1ull << c;
+    }
+    out[idx] = bits ^ flip[word];
+}
+
 // ------------------------------------------------------------------------------ wreg
 
 // A packed pixel of zeros (= every channel +1): what a tap outside the image reads.  Never
@@ -353,6 +392,17 @@ hipError_t launch_bconv_reference(const uint64_t* a, const uint64_t* w, int32_t*
     const int64_t blocks = (total + 255) / 256;
     bconv_reference_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream>>>(a, w, y, s,
                                                                                          total);
+    return hipGetLastError();
+}
+
+hipError_t launch_bconv_bnsign_reference(const uint64_t* a, const uint64_t* w, const int32_t* thr,
+                                         const uint64_t* flip, uint64_t* out, const ConvShape& s,
+                                         hipStream_t stream)
+{
+    const int64_t total = static_cast<int64_t>(s.N) * s.Ho * s.Wo * ((s.Cout + 63) / 64);
+    const int64_t blocks = (total + 255) / 256;
+    bconv_bnsign_reference_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream>>>(
+        a, w, thr, flip, out, s, total);
     return hipGetLastError();
 }
 

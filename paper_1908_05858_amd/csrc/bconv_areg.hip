@@ -106,17 +106,38 @@ __device__ __forceinline__ void store_out4(void* dst, const int4& o)
         *reinterpret_cast<v4i*>(dst) = v;
 }
 
+// Fused threshold: bits = (bits << 2) | (d0 > t0) << 1 | (d1 > t1) for two output channels,
+// where d is the popcount sum and t the per-channel bound (wave-uniform, SGPRs written by SALU
+// instructions).  Each compare result goes straight into the carry input of an add-with-carry
+// of bits to itself.  The second compare and the s_nop give the two wait states gfx950 needs
+// between a VALU write of an SGPR pair and a VALU read of it.
+__device__ __forceinline__ void shift_in_2(uint32_t& bits, int d0, int d1, int t0, int t1)
+{
+    uint64_t c1;
+    asm("v_cmp_lt_i32_e32 vcc, %4, %2\n\t"
+        "v_cmp_lt_i32_e64 %1, %5, %3\n\t"
+        "s_nop 0\n\t"
+        "v_addc_co_u32_e32 %0, vcc, %0, %0, vcc\n\t"
+        "v_addc_co_u32_e64 %0, %1, %0, %0, %1"
+        : "+v"(bits), "=&s"(c1)
+        : "v"(d0), "v"(d1), "s"(t0), "s"(t1)
+        : "vcc");
+}
+
 // Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
 // and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
 // (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
 //   TR = 16 or 32 (transposed store through LDS): CG = TR.   TR = 0, direct 16-byte stores:
-//   CG = 8 (Cw = 1) or 4.
+//   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 and four
+//   groups (one 64-bit output word) form the unit of work distribution.
+constexpr int kBits = -1;
 constexpr int kDC = 6;
 template <int CW, int TR>
 struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
-    static constexpr int CG = TR ? TR : (CW == 1 ? 8 : 4);
+    static constexpr int CG = TR > 0 ? TR : (TR == kBits ? 16 : (CW == 1 ? 8 : 4));
+    static constexpr int GPU = (TR == kBits) ? 4 : 1;  // groups per unit of work distribution
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
@@ -157,11 +178,12 @@ template <int CW, int S, int TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
-    int n_ranges, int base_groups, int rem_groups)
+    int n_ranges, int base_groups, int rem_groups, const int32_t* __restrict__ thr,
+    const uint2* __restrict__ flip)
 {
     using G = AregGeom<CW, TR>;
-    // 64 pixels x 16 channels of int32 per wavefront, used only by the transposed store
-    __shared__ int32_t tile_lds[TR ? 4 * 64 * TR : 4];
+    // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
+    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : 4];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -169,10 +191,13 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     if (gw >= n_ranges)
         return;  // the grid is rounded up to whole workgroups
     // balanced contiguous partition of (tile, channel group) pairs, channel group fastest
+    // (counted in units of G::GPU groups)
     int g = gw * base_groups + (gw < rem_groups ? gw : rem_groups);
-    const int g_end = g + base_groups + (gw < rem_groups ? 1 : 0);
-    if (g >= g_end)
+    int g_end_ = g + base_groups + (gw < rem_groups ? 1 : 0);
+    if (g >= g_end_)
         return;
+    g *= G::GPU;
+    const int g_end = g_end_ * G::GPU;
     int tile = g / groups_per_tile;
     int cgi = g - tile * groups_per_tile;
 
@@ -224,6 +249,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 
     uint32_t sb0[G::SB], sb1[G::SB];
     areg_load_unit<CW, TR, 0>(sb0, w, cgi * G::CG);
+    uint32_t half_bits = 0, word_lo = 0;  // fused bit-pack output under construction
 
     for (; g < g_end; ++g) {
         int ncgi = cgi + 1, ntile = tile;
@@ -256,7 +282,30 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             schedule_fence();
         });
 
-        if constexpr (TR != 0) {
+        if constexpr (TR == kBits) {
+            // Fused threshold + bit-pack: y < thr  <=>  K - 2d < thr  <=>  d > (K - thr) >> 1.
+            // Channels are shifted in ascending order, so a finished 32-channel half is
+            // bit-reversed; two halves and the flip mask make one output word per pixel.
+            const int gq = cgi & 3;  // position of this group in its 64-channel word
+            if ((gq & 1) == 0)
+                half_bits = 0;
+            const int32_t* tp = thr + cgi * 16;
+#pragma unroll
+            for (int q = 0; q < 16; q += 2)
+                shift_in_2(half_bits, acc[q], acc[q + 1], (K - tp[q]) >> 1, (K - tp[q + 1]) >> 1);
+            if (gq == 1)
+                word_lo = __builtin_bitreverse32(half_bits);
+            if (gq == 3) {
+                const uint2 fl = flip[cgi >> 2];
+                uint2 o;
+                o.x = word_lo ^ fl.x;
+                o.y = __builtin_bitreverse32(half_bits) ^ fl.y;
+                if (pvalid) {
+                    uint2* dst = reinterpret_cast<uint2*>(y);
+                    dst[static_cast<size_t>(tile * 64 + lane) * (groups_per_tile >> 2) + (cgi >> 2)] = o;
+                }
+            }
+        } else if constexpr (TR != 0) {
             // Row P of the wavefront's LDS slice holds pixel P's TR channels as QPR 16-byte quads.
             // Quad j sits in column j ^ swz(P), which makes both the row-wise writes and the
             // transposed reads free of bank conflicts (a 64-byte row covers half the banks, so
@@ -334,7 +383,8 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 
 template <int CW, int S, int TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
-                            hipStream_t stream)
+                            hipStream_t stream, const int32_t* thr = nullptr,
+                            const uint2* flip = nullptr)
 {
     using G = AregGeom<CW, TR>;
     static_assert(G::UNITS % 2 == 0 && G::KD % kDC == 0, "pipeline geometry");
@@ -343,7 +393,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 63) / 64;
     const int groups_per_tile = s.Cout / G::CG;
-    const int64_t n_groups64 = tiles * groups_per_tile;
+    const int64_t n_groups64 = tiles * (groups_per_tile / G::GPU);  // units of work
     if (n_groups64 > 0x3fffffff)
         return hipErrorNotSupported;
     const int n_groups = static_cast<int>(n_groups64);
@@ -358,7 +408,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
                        s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
-                       rem_groups);
+                       rem_groups, thr, flip);
     return hipGetLastError();
 }
 
@@ -386,7 +436,40 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     return launch_areg_inst<CW, 2, 0>(a, w, y, s, stream);
 }
 
+template <int CW>
+hipError_t launch_bits_s(const uint32_t* a, const uint32_t* w, uint64_t* out, const ConvShape& s,
+                         hipStream_t stream, const int32_t* thr, const uint2* flip)
+{
+    int32_t* y = reinterpret_cast<int32_t*>(out);
+    if (s.stride == 1)
+        return launch_areg_inst<CW, 1, kBits>(a, w, y, s, stream, thr, flip);
+    return launch_areg_inst<CW, 2, kBits>(a, w, y, s, stream, thr, flip);
+}
+
 }  // namespace
+
+bool bconv_bnsign_areg_supports(const ConvShape& s)
+{
+    return s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) &&
+           (s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8) && s.Cout % 64 == 0;
+}
+
+hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const int32_t* thr,
+                                    const uint64_t* flip, uint64_t* out, const ConvShape& s,
+                                    hipStream_t stream)
+{
+    if (!bconv_bnsign_areg_supports(s))
+        return hipErrorNotSupported;
+    const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
+    const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
+    const uint2* f2 = reinterpret_cast<const uint2*>(flip);
+    switch (s.Cw) {
+        case 1: return launch_bits_s<1>(a32, w32, out, s, stream, thr, f2);
+        case 2: return launch_bits_s<2>(a32, w32, out, s, stream, thr, f2);
+        case 4: return launch_bits_s<4>(a32, w32, out, s, stream, thr, f2);
+        default: return launch_bits_s<8>(a32, w32, out, s, stream, thr, f2);
+    }
+}
 
 bool bconv_areg_supports(const ConvShape& s, const void* y)
 {

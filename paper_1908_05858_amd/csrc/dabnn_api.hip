@@ -4,6 +4,8 @@
 
 #include "launch.h"
 
+#include <cmath>
+
 namespace {
 
 bool aligned(const void* p, uintptr_t a)
@@ -139,6 +141,66 @@ int dabnn_bconv2d(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H
 {
     return dabnn_bconv2d_algo(a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad, DABNN_ALGO_AUTO,
                               stream);
+}
+
+int dabnn_bconv2d_bnsign(const uint64_t* a, const uint64_t* w, const int32_t* thr,
+                         const uint64_t* flip, uint64_t* out, int N, int H, int W, int Cin,
+                         int Cout, int kh, int kw, int stride, int pad, void* stream)
+{
+    if (!a || !w || !thr || !flip || !out)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (!aligned(a, 8) || !aligned(w, 8) || !aligned(thr, 4) || !aligned(flip, 8) || !aligned(out, 8))
+        return DABNN_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = dabnn::bconv_bnsign_areg_supports(s)
+                             ? dabnn::launch_bconv_bnsign_areg(a, w, thr, flip, out, s, st)
+                             : dabnn::launch_bconv_bnsign_reference(a, w, thr, flip, out, s, st);
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_bn_thresholds(const float* gamma, const float* beta, const float* mean, const float* var,
+                        float eps, int Cout, int K, int32_t* thr, uint64_t* flip)
+{
+    if (!gamma || !beta || !mean || !var || !thr || !flip)
+        return DABNN_ERR_NULL;
+    if (Cout <= 0 || K <= 0 || K >= (1 << 30))
+        return DABNN_ERR_SHAPE;
+    for (int j = 0; j < (Cout + 63) / 64; ++j)
+        flip[j] = 0;
+    for (int c = 0; c < Cout; ++c) {
+        const double g = gamma[c], b = beta[c], m = mean[c];
+        const double sd = std::sqrt(static_cast<double>(var[c]) + static_cast<double>(eps));
+        // the batch-norm output for the integer conv value y, in the order the layer is defined
+        auto negative = [&](int y) { return g * (static_cast<double>(y) - m) / sd + b < 0.0; };
+        // z is monotone in y (rounding keeps monotonicity), so the set {y : z < 0} is a prefix
+        // (gamma > 0), a suffix (gamma < 0) or all/nothing: find the boundary by bisection.
+        const bool lo_neg = negative(-K), hi_neg = negative(K);
+        int t;
+        bool fl;
+        if (lo_neg == hi_neg) {  // constant on [-K, K] (also gamma == 0 and NaN parameters)
+            t = -K;              // y < -K never holds
+            fl = lo_neg;
+        } else {
+            int lo = -K, hi = K;  // negative(lo) != negative(hi): the answer flips in (lo, hi]
+            while (hi - lo > 1) {
+                const int mid = lo + (hi - lo) / 2;
+                if (negative(mid) == lo_neg)
+                    lo = mid;
+                else
+                    hi = mid;
+            }
+            t = hi;               // first y where the sign differs from the one at -K
+            fl = !lo_neg;         // prefix negative: bit = y < t; suffix negative: bit = !(y < t)
+        }
+        thr[c] = t;
+        if (fl)
+            flip[c / 64] |= 1ull << (c % 64);
+    }
+    return DABNN_OK;
 }
 
 int dabnn_bconv2d_pick_algo(int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,

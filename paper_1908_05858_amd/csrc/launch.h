@@ -24,6 +24,14 @@ hipError_t launch_bconv_wreg(const uint64_t* a, const uint64_t* w, int32_t* y,
                              const ConvShape& s, hipStream_t stream);
 hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y,
                              const ConvShape& s, hipStream_t stream);
+// Fused conv + threshold + bit-pack (Sec. 2.1.1, fused BN-binarization): tuned and reference.
+hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const int32_t* thr,
+                                    const uint64_t* flip, uint64_t* out, const ConvShape& s,
+                                    hipStream_t stream);
+hipError_t launch_bconv_bnsign_reference(const uint64_t* a, const uint64_t* w, const int32_t* thr,
+                                         const uint64_t* flip, uint64_t* out, const ConvShape& s,
+                                         hipStream_t stream);
+bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);
 

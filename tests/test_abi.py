@@ -83,3 +83,51 @@ def test_pick_algo(lib):
     assert lib.dabnn_bconv2d_pick_algo(256, 56, 56, 64, 64, 3, 3, 1, 1) in (2, 3)
     assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 5, 5, 1, 2) == 1
     assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 3, 3, 0, 1) == -1
+
+
+def test_bn_thresholds_match_fp64_batch_norm_for_every_integer(lib):
+    """The host helper, exhaustively: for every integer y in [-K, K] the threshold rule equals
+    the sign of the fp64 batch-norm (numpy, evaluated in the same order)."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    C, K = 200, 576
+    gamma = rng.uniform(-2, 2, C).astype(np.float32)
+    gamma[::9] = 0.0
+    gamma[1] = 1e-30
+    beta = rng.normal(0, 1.0, C).astype(np.float32)
+    beta[3] = 0.0
+    mean = rng.normal(0, 60.0, C).astype(np.float32)
+    mean[3] = 17.0          # z is exactly 0 at y = 17: counts as +1
+    mean[5] = 1e9           # never crosses zero inside [-K, K]
+    var = rng.uniform(0.1, 90.0, C).astype(np.float32)
+    eps = np.float32(1e-5)
+    thr = np.empty(C, np.int32)
+    flip = np.empty((C + 63) // 64, np.uint64)
+    P = ctypes.c_void_p
+    rc = lib.dabnn_bn_thresholds(P(gamma.ctypes.data), P(beta.ctypes.data), P(mean.ctypes.data),
+                                 P(var.ctypes.data), ctypes.c_float(eps), C, K, P(thr.ctypes.data),
+                                 P(flip.ctypes.data))
+    assert rc == 0
+    y = np.arange(-K, K + 1, dtype=np.float64)[:, None]
+    z = gamma.astype(np.float64) * (y - mean.astype(np.float64)) / np.sqrt(var.astype(np.float64) + np.float64(eps)) \
+        + beta.astype(np.float64)
+    want = z < 0
+    fl = np.array([(int(flip[c // 64]) >> (c % 64)) & 1 for c in range(C)], dtype=bool)
+    got = (np.arange(-K, K + 1)[:, None] < thr[None, :]) ^ fl[None, :]
+    assert np.array_equal(got, want)
+    assert np.all(np.abs(thr) <= K + 1)
+    # bad arguments
+    assert lib.dabnn_bn_thresholds(P(0), P(beta.ctypes.data), P(mean.ctypes.data), P(var.ctypes.data),
+                                   ctypes.c_float(eps), C, K, P(thr.ctypes.data), P(flip.ctypes.data)) == 1
+    assert lib.dabnn_bn_thresholds(P(gamma.ctypes.data), P(beta.ctypes.data), P(mean.ctypes.data),
+                                   P(var.ctypes.data), ctypes.c_float(eps), 0, K, P(thr.ctypes.data),
+                                   P(flip.ctypes.data)) == 2
+
+
+def test_bnsign_bad_arguments(lib):
+    P = ctypes.c_void_p
+    a, w, t, f, o = P(0x10000), P(0x20000), P(0x30000), P(0x40000), P(0x50000)
+    assert lib.dabnn_bconv2d_bnsign(a, w, P(0), f, o, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d_bnsign(a, w, t, f, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d_bnsign(a, w, t, f, o, 1, 4, 4, 64, 0, 3, 3, 1, 1, None) == 2
+    assert lib.dabnn_bconv2d_bnsign(a, w, t, P(0x40004), o, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3

@@ -183,6 +183,82 @@ def test_kernel_variants(dabnn, oracle, env, monkeypatch):
         run_conv(dabnn, oracle, *shape, seed=31337 + sum(shape), algo=algo)
 
 
+# ------------------------------------------------------------------------------- fused BN + sign
+
+def _bn_params(C, seed):
+    rng = np.random.default_rng(seed)
+    gamma = rng.uniform(-1.5, 1.5, C).astype(np.float32)
+    gamma[::7] = 0.0
+    beta = rng.normal(0, 0.5, C).astype(np.float32)
+    mean = rng.normal(0, 8.0, C).astype(np.float32)
+    var = rng.uniform(0.5, 40.0, C).astype(np.float32)
+    return gamma, beta, mean, var
+
+
+BNSIGN_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (1, 14, 14, 64, 64, 3, 1, 1),
+    (3, 28, 28, 128, 128, 3, 1, 1),
+    (2, 56, 56, 64, 128, 3, 2, 1),
+    (5, 14, 14, 256, 256, 3, 1, 1),
+    (4, 14, 14, 256, 512, 3, 2, 1),
+    (9, 7, 7, 512, 512, 3, 1, 1),
+    (2, 9, 13, 80, 192, 3, 1, 1),       # tail in Cin, three output words
+    (70, 3, 3, 64, 64, 3, 1, 1),        # ragged last tile
+    (2, 9, 9, 64, 70, 3, 1, 1),         # Cout % 64 != 0: reference kernel, tail in the output word
+    (1, 12, 12, 64, 16, 5, 1, 2),       # 5x5: reference kernel
+    (2, 6, 6, 200, 33, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("shape", BNSIGN_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_bconv2d_bnsign(dabnn, oracle, shape):
+    """Fused conv + batch-norm threshold + bit-pack against sign(BN(conv)) of the oracle (fp64
+    batch-norm), word for word."""
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("bnsign", shape, flush=True)
+    x = wl.activations((N, H, W, Cin), 7000 + sum(shape))
+    wf = wl.weights((Cout, k, k, Cin), 7001 + sum(shape))
+    gamma, beta, mean, var = _bn_params(Cout, 7002 + sum(shape))
+    eps = 1e-5
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, eps, k * k * Cin)
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    Ho, Wo = oracle.conv_out_dim(H, k, stride, pad), oracle.conv_out_dim(W, k, stride, pad)
+    words_out = (Cout + 63) // 64
+    buf = torch.full((N * Ho * Wo * words_out + 32,), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+    out = buf[16:16 + N * Ho * Wo * words_out].view(N, Ho, Wo, words_out)
+    dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, stride, pad, out=out)
+    want = oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, eps, stride, pad)
+    assert torch.all(buf[:16] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-16:] == 0x5A5A5A5A5A5A5A5A)
+    got = words(out)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} of {got.size} words differ, first at {bad[0]}: "
+                             f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}")
+
+
+def test_bnsign_chain_feeds_next_layer(dabnn, oracle):
+    """Two fused layers back to back: the packed output of the first is the packed input of the
+    second, with no int32 tensor and no bit-pack pass in between."""
+    N = 3
+    x = wl.activations((N, 28, 28, 128), 7100)
+    w1 = wl.weights((128, 3, 3, 128), 7101)
+    w2 = wl.weights((256, 3, 3, 128), 7102)
+    bn1, bn2 = _bn_params(128, 7103), _bn_params(256, 7104)
+    eps = 1e-5
+    t1 = dabnn.bn_thresholds(*bn1, eps, 9 * 128)
+    t2 = dabnn.bn_thresholds(*bn2, eps, 9 * 128)
+    a0 = dabnn.bitpack(gpu(x))
+    a1 = dabnn.bconv2d_bnsign(a0, dabnn.pack_weights(gpu(w1)), *t1, 128, 1, 1)
+    a2 = dabnn.bconv2d_bnsign(a1, dabnn.pack_weights(gpu(w2)), *t2, 128, 2, 1)
+    o1 = oracle.bconv2d_bnsign(x, w1, *bn1, eps, 1, 1)
+    assert np.array_equal(words(a1), o1)
+    # unpack the oracle's first-layer bits to +-1 floats for its second layer
+    bits = np.unpackbits(o1.view(np.uint8), axis=-1, bitorder="little")[..., :128]
+    x1 = np.where(bits == 1, -1.0, 1.0).astype(np.float32)
+    assert np.array_equal(words(a2), oracle.bconv2d_bnsign(x1, w2, *bn2, eps, 2, 1))
+
+
 def test_closed_forms_on_gpu(dabnn):
     """All-equal gives +K, all-opposite gives -K, with the border taps counted as +1."""
     for (N, H, W, Cin, Cout, k, s, p) in [(2, 14, 14, 64, 64, 3, 1, 1), (1, 9, 9, 80, 70, 3, 2, 1)]:

@@ -278,3 +278,65 @@ def test_glue_closed_form(oracle):
     out2 = oracle.glue(x, y2, np.ones(2 * C, np.float32), np.zeros(2 * C, np.float32), 4, 2)
     pooled = x.reshape(N, 2, 2, 2, 2, C).mean(axis=(2, 4))
     assert np.allclose(out2, np.concatenate([pooled, pooled], axis=-1))
+
+
+# ----------------------------------------------------------------------------- fused BN + sign
+
+def _bn_params(C, seed):
+    rng = np.random.default_rng(seed)
+    gamma = rng.uniform(-1.5, 1.5, C).astype(np.float32)
+    gamma[::7] = 0.0                                   # degenerate channels: constant output
+    beta = rng.normal(0, 0.5, C).astype(np.float32)
+    mean = rng.normal(0, 8.0, C).astype(np.float32)
+    var = rng.uniform(0.5, 40.0, C).astype(np.float32)
+    return gamma, beta, mean, var
+
+
+@pytest.mark.parametrize("shape", [(1, 5, 6, 64, 70, 3, 1, 1), (2, 7, 7, 80, 64, 3, 2, 1), (1, 4, 4, 7, 3, 1, 1, 0)])
+def test_bnsign_against_torch_batch_norm(oracle, shape):
+    """sign(BN(conv)) with torch's CPU batch_norm in float64 on the (already pinned) integer conv
+    output, packed with numpy.packbits."""
+    N, H, W, Cin, Cout, k, s, p = shape
+    x = wl.activations((N, H, W, Cin), 91)
+    wf = wl.weights((Cout, k, k, Cin), 92)
+    gamma, beta, mean, var = _bn_params(Cout, 93)
+    eps = 1e-5
+    got = oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, eps, s, p)
+    y = torch.from_numpy(oracle.bconv2d(x, wf, s, p)).double().permute(0, 3, 1, 2)
+    z = torch.nn.functional.batch_norm(y, torch.from_numpy(mean).double(), torch.from_numpy(var).double(),
+                                       torch.from_numpy(gamma).double(), torch.from_numpy(beta).double(),
+                                       training=False, eps=eps).permute(0, 2, 3, 1).numpy()
+    # torch evaluates (y - mean) / sqrt(var + eps) * gamma + beta; the oracle multiplies first.
+    # Away from |z| ~ 1e-12 the sign is the same; such ties do not occur with these parameters.
+    assert np.abs(z[z != 0]).min() > 1e-9
+    words = (Cout + 63) // 64
+    bits = np.zeros(z.shape[:-1] + (words * 64,), dtype=bool)
+    bits[..., :Cout] = z < 0
+    ref = np.packbits(bits, axis=-1, bitorder="little").view("<u8")
+    assert np.array_equal(got, ref)
+
+
+def test_bnsign_closed_forms(oracle):
+    N, H, W, Cin, Cout, k, s, p = 1, 6, 5, 64, 66, 3, 1, 1
+    x = wl.activations((N, H, W, Cin), 94)
+    wf = wl.weights((Cout, k, k, Cin), 95)
+    y = oracle.bconv2d(x, wf, s, p)
+    one, zero = np.ones(Cout, np.float32), np.zeros(Cout, np.float32)
+
+    def pack(b):
+        full = np.zeros(b.shape[:-1] + (128,), dtype=bool)
+        full[..., :Cout] = b
+        return np.packbits(full, axis=-1, bitorder="little").view("<u8")
+
+    # identity batch-norm: the bit is y < 0 (y == 0 counts as +1)
+    assert np.array_equal(oracle.bconv2d_bnsign(x, wf, one, zero, zero, one, 0.0, s, p), pack(y < 0))
+    # a pure threshold: gamma = 2, mean = m  ->  bit = y < m
+    m = np.arange(Cout, dtype=np.float32) - 30.5
+    assert np.array_equal(oracle.bconv2d_bnsign(x, wf, 2 * one, zero, m, one, 0.0, s, p), pack(y < m))
+    # negative gamma reverses the comparison
+    assert np.array_equal(oracle.bconv2d_bnsign(x, wf, -one, zero, m, one, 0.0, s, p), pack(y > m))
+    # a huge shift decides everything: all +1 (no bit) or all -1 (every real channel, tail still 0)
+    big = 1e6 * one
+    assert not oracle.bconv2d_bnsign(x, wf, one, big, zero, one, 0.0, s, p).any()
+    allneg = oracle.bconv2d_bnsign(x, wf, one, -big, zero, one, 0.0, s, p)
+    assert np.all(allneg[..., 0] == np.uint64(0xFFFFFFFFFFFFFFFF)) and np.all(allneg[..., 1] == np.uint64(3))
