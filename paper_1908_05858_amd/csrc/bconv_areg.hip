@@ -106,30 +106,21 @@ __device__ __forceinline__ void store_out4(void* dst, const int4& o)
         *reinterpret_cast<v4i*>(dst) = v;
 }
 
-// Fused threshold: bits = (bits << 2) | (d0 > t0) << 1 | (d1 > t1) for two output channels,
-// where d is the popcount sum and t the per-channel bound (wave-uniform, SGPRs written by SALU
-// instructions).  Each compare result goes straight into the carry input of an add-with-carry
-// of bits to itself.  The second compare and the s_nop give the two wait states gfx950 needs
-// between a VALU write of an SGPR pair and a VALU read of it.
-__device__ __forceinline__ void shift_in_2(uint32_t& bits, int d0, int d1, int t0, int t1)
+// Fused threshold: bits = (bits << 1) | (y < thr) for one output channel, with y = K - 2d (d the
+// popcount sum) and kt = K - thr:  y < thr  <=>  kt - 2d < 0.  Plain VALU arithmetic: the sign bit
+// of kt - 2d is shifted in with v_alignbit_b32, no lane mask ever goes through an SGPR pair.
+__device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
 {
-    uint64_t c1;
-    asm("v_cmp_lt_i32_e32 vcc, %4, %2\n\t"
-        "v_cmp_lt_i32_e64 %1, %5, %3\n\t"
-        "s_nop 0\n\t"
-        "v_addc_co_u32_e32 %0, vcc, %0, %0, vcc\n\t"
-        "v_addc_co_u32_e64 %0, %1, %0, %0, %1"
-        : "+v"(bits), "=&s"(c1)
-        : "v"(d0), "v"(d1), "s"(t0), "s"(t1)
-        : "vcc");
+    const int t = kt - 2 * d;  // |kt|, 2d < 2^31: no overflow
+    bits = __builtin_amdgcn_alignbit(bits, static_cast<uint32_t>(t), 31);
 }
 
 // Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
 // and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
 // (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
 //   TR = 16 or 32 (transposed store through LDS): CG = TR.   TR = 0, direct 16-byte stores:
-//   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 and four
-//   groups (one 64-bit output word) form the unit of work distribution.
+//   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
+//   an output word).
 constexpr int kBits = -1;
 constexpr int kDC = 6;
 template <int CW, int TR>
@@ -137,7 +128,6 @@ struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
     static constexpr int CG = TR > 0 ? TR : (TR == kBits ? 16 : (CW == 1 ? 8 : 4));
-    static constexpr int GPU = (TR == kBits) ? 4 : 1;  // groups per unit of work distribution
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
@@ -191,13 +181,11 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     if (gw >= n_ranges)
         return;  // the grid is rounded up to whole workgroups
     // balanced contiguous partition of (tile, channel group) pairs, channel group fastest
-    // (counted in units of G::GPU groups)
     int g = gw * base_groups + (gw < rem_groups ? gw : rem_groups);
-    int g_end_ = g + base_groups + (gw < rem_groups ? 1 : 0);
-    if (g >= g_end_)
+    const int g_begin = g;
+    const int g_end = g + base_groups + (gw < rem_groups ? 1 : 0);
+    if (g >= g_end)
         return;
-    g *= G::GPU;
-    const int g_end = g_end_ * G::GPU;
     int tile = g / groups_per_tile;
     int cgi = g - tile * groups_per_tile;
 
@@ -215,19 +203,22 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         const int ho = r / Wo;
         const int wo = r - ho * Wo;
         ybase = static_cast<uint32_t>(pc) * static_cast<uint32_t>(Cout);
+        // Pixel index of the window's top-left tap; taps are addressed as a uniform base plus a
+        // 32-bit byte offset (the launcher checks that the tensor fits), invalid taps read
+        // offset 0 and are masked.
+        const int hi0 = ho * S - pad, wi0 = wo * S - pad;
+        const int top_left = (n * H + hi0) * W + wi0;
+        const char* base = reinterpret_cast<const char*>(a);
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
-            const int hi = ho * S - pad + i;
-            const bool rv = static_cast<unsigned>(hi) < static_cast<unsigned>(H);
-            const int hic = rv ? hi : 0;
+            const bool rv = static_cast<unsigned>(hi0 + i) < static_cast<unsigned>(H);
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
-                const int wi = wo * S - pad + j;
-                const bool v = rv && static_cast<unsigned>(wi) < static_cast<unsigned>(W);
-                const int wic = v ? wi : 0;
+                const bool v = rv && static_cast<unsigned>(wi0 + j) < static_cast<unsigned>(W);
                 const uint32_t keep = v ? 0xffffffffu : 0u;
-                const uint32_t* src =
-                    a + (static_cast<size_t>(n * H + hic) * W + wic) * G::D;
+                const uint32_t off =
+                    v ? static_cast<uint32_t>(top_left + i * W + j) * (G::D * 4u) : 0u;
+                const char* src = base + off;
                 if constexpr (G::D == 2) {
                     const uint2 u = *reinterpret_cast<const uint2*>(src);
                     areg[(i * 3 + j) * 2 + 0] = u.x & keep;
@@ -235,7 +226,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                 } else {
 #pragma unroll
                     for (int d = 0; d < G::D; d += 4) {
-                        const uint4 u = *reinterpret_cast<const uint4*>(src + d);
+                        const uint4 u = *reinterpret_cast<const uint4*>(src + d * 4);
                         areg[(i * 3 + j) * G::D + d + 0] = u.x & keep;
                         areg[(i * 3 + j) * G::D + d + 1] = u.y & keep;
                         areg[(i * 3 + j) * G::D + d + 2] = u.z & keep;
@@ -249,7 +240,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 
     uint32_t sb0[G::SB], sb1[G::SB];
     areg_load_unit<CW, TR, 0>(sb0, w, cgi * G::CG);
-    uint32_t half_bits = 0, word_lo = 0;  // fused bit-pack output under construction
+    uint32_t bits32 = 0;  // fused bit-pack output under construction
 
     for (; g < g_end; ++g) {
         int ncgi = cgi + 1, ntile = tile;
@@ -259,6 +250,23 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         }
 
         int acc[G::CG];
+        // The group's 16 thresholds, fetched with vector loads at the start of the group (every
+        // lane reads the same 64 bytes) so that they neither occupy SGPRs nor disturb the
+        // scalar-load pipeline; they are first used after the last unit.
+        int thr_v[TR == kBits ? 16 : 1];
+        if constexpr (TR == kBits) {
+            uint32_t lane_off = 0;
+            asm volatile("" : "+v"(lane_off));  // keeps the address per-lane: a vector load
+            const int4* tp = reinterpret_cast<const int4*>(thr + cgi * 16 + lane_off);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int4 t = tp[q];
+                thr_v[4 * q + 0] = t.x;
+                thr_v[4 * q + 1] = t.y;
+                thr_v[4 * q + 2] = t.z;
+                thr_v[4 * q + 3] = t.w;
+            }
+        }
 
         // Software pipeline: while unit u feeds the VALU, unit u+1 is in flight.
         static_for<0, G::UNITS>([&](auto uc) {
@@ -283,27 +291,30 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         });
 
         if constexpr (TR == kBits) {
-            // Fused threshold + bit-pack: y < thr  <=>  K - 2d < thr  <=>  d > (K - thr) >> 1.
-            // Channels are shifted in ascending order, so a finished 32-channel half is
-            // bit-reversed; two halves and the flip mask make one output word per pixel.
-            const int gq = cgi & 3;  // position of this group in its 64-channel word
-            if ((gq & 1) == 0)
-                half_bits = 0;
-            const int32_t* tp = thr + cgi * 16;
+            // Fused threshold + bit-pack: y < thr  <=>  (K - thr) - 2d < 0.  The 16 channels are
+            // shifted in in ascending order and bit-reversed into place afterwards.  An even
+            // group whose odd partner belongs to this wavefront too is held back, and the pair
+            // leaves as one 32-bit store; a group whose partner belongs to a neighbouring
+            // wavefront leaves as a 16-bit store (distinct bytes of the word: no race).
+            const bool odd = (cgi & 1) != 0;
+            if (!odd)
+                bits32 = 0;
 #pragma unroll
-            for (int q = 0; q < 16; q += 2)
-                shift_in_2(half_bits, acc[q], acc[q + 1], (K - tp[q]) >> 1, (K - tp[q + 1]) >> 1);
-            if (gq == 1)
-                word_lo = __builtin_bitreverse32(half_bits);
-            if (gq == 3) {
-                const uint2 fl = flip[cgi >> 2];
-                uint2 o;
-                o.x = word_lo ^ fl.x;
-                o.y = __builtin_bitreverse32(half_bits) ^ fl.y;
-                if (pvalid) {
-                    uint2* dst = reinterpret_cast<uint2*>(y);
-                    dst[static_cast<size_t>(tile * 64 + lane) * (groups_per_tile >> 2) + (cgi >> 2)] = o;
-                }
+            for (int q = 0; q < 16; ++q)
+                shift_in(bits32, acc[q], K - thr_v[q]);
+            const uint2 fl = flip[cgi >> 2];
+            const uint32_t fl32 = (cgi & 2) ? fl.y : fl.x;
+            const size_t half_index =
+                static_cast<size_t>(tile * 64 + lane) * (groups_per_tile >> 1) + (cgi >> 1);
+            const uint32_t rev = __builtin_bitreverse32(bits32);
+            if (odd && g > g_begin) {
+                if (pvalid)
+                    reinterpret_cast<uint32_t*>(y)[half_index] = rev ^ fl32;
+            } else if (odd || g + 1 >= g_end) {
+                const uint32_t fl16 = odd ? (fl32 >> 16) : (fl32 & 0xffffu);
+                if (pvalid)
+                    reinterpret_cast<uint16_t*>(y)[2 * half_index + (odd ? 1 : 0)] =
+                        static_cast<uint16_t>((rev >> 16) ^ fl16);
             }
         } else if constexpr (TR != 0) {
             // Row P of the wavefront's LDS slice holds pixel P's TR channels as QPR 16-byte quads.
@@ -393,7 +404,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 63) / 64;
     const int groups_per_tile = s.Cout / G::CG;
-    const int64_t n_groups64 = tiles * (groups_per_tile / G::GPU);  // units of work
+    const int64_t n_groups64 = tiles * groups_per_tile;
     if (n_groups64 > 0x3fffffff)
         return hipErrorNotSupported;
     const int n_groups = static_cast<int>(n_groups64);
@@ -448,9 +459,18 @@ hipError_t launch_bits_s(const uint32_t* a, const uint32_t* w, uint64_t* out, co
 
 }  // namespace
 
+// The kernels address the activation tensor and (on the direct-store path) the output with
+// 32-bit element offsets.
+static bool areg_offsets_fit(const ConvShape& s)
+{
+    const int64_t act_dwords = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 2;
+    const int64_t out_elems = static_cast<int64_t>(s.N) * s.Ho * s.Wo * s.Cout;
+    return act_dwords < (int64_t{1} << 31) && out_elems < (int64_t{1} << 31);
+}
+
 bool bconv_bnsign_areg_supports(const ConvShape& s)
 {
-    return s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) &&
+    return areg_offsets_fit(s) && s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) &&
            (s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8) && s.Cout % 64 == 0;
 }
 
@@ -478,7 +498,7 @@ bool bconv_areg_supports(const ConvShape& s, const void* y)
     if (!(s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8))
         return false;
     const int cg = (s.Cw == 1) ? 8 : 4;
-    return s.Cout % cg == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+    return areg_offsets_fit(s) && s.Cout % cg == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
 }
 
 hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, const ConvShape& s,
