@@ -6,7 +6,8 @@ package.  It imports nothing from the GPU package and the GPU package imports no
 
 What each function computes, with the passage it follows, is stated in ``dabnn_oracle.c``:
 ``sign`` / ``bitpack`` follow Sec. 2.1.1; ``bconv2d`` is the +-1 float cross-correlation that
-Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal; ``bconv2d_bnsign`` is that convolution followed by
+Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal (``bconv2d_zeropad``: the same with the zero padding
+of the ONNX Convolution operator the paper builds on); ``bconv2d_bnsign`` is that convolution followed by
 fp64 batch-norm and the sign (fused BN-binarization, Sec. 2.1.1); ``glue`` only generates inputs.
 
 Every function here is pinned by ``tests/test_oracle_pins.py`` (closed forms, invariants, brute
@@ -48,11 +49,13 @@ def _load():
     lib.oracle_bitpack.argtypes = [vp, vp, i64, i32, i32]
     lib.oracle_conv_out_dim.argtypes = [i32] * 4
     lib.oracle_bconv2d.argtypes = [vp, vp, vp] + [i32] * 9
+    lib.oracle_bconv2d_zeropad.argtypes = [vp, vp, vp] + [i32] * 9
     lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
     lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
     lib.oracle_bconv2d_bnsign.argtypes = [vp] * 6 + [ctypes.c_float, vp] + [i32] * 9
     for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
-              lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign):
+              lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign,
+              lib.oracle_bconv2d_zeropad):
         f.restype = i32
     _lib = lib
     return lib
@@ -105,6 +108,28 @@ def bconv2d_signed(A, Wt, stride=1, pad=0):
     _check(_load().oracle_bconv2d(A.ctypes.data, Wt.ctypes.data, Y.ctypes.data, N, H, W, Cin, Cout,
                                   kh, kw, stride, pad), "bconv2d")
     return Y
+
+
+def bconv2d_zeropad_signed(A, Wt, stride=1, pad=0):
+    """+-1 float cross-correlation with ZERO padding (ONNX Convolution; Table 1 caption, Sec. 3):
+    same shapes as bconv2d_signed, out-of-image taps contribute nothing."""
+    A, Wt = _f32(A), _f32(Wt)
+    N, H, W, Cin = A.shape
+    Cout, kh, kw, Cin2 = Wt.shape
+    if Cin != Cin2:
+        raise ValueError("channel mismatch")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    Y = np.empty((N, Ho, Wo, Cout), dtype=np.int32)
+    _check(_load().oracle_bconv2d_zeropad(A.ctypes.data, Wt.ctypes.data, Y.ctypes.data, N, H, W, Cin,
+                                          Cout, kh, kw, stride, pad), "bconv2d_zeropad")
+    return Y
+
+
+def bconv2d_zeropad(x, w, stride=1, pad=0, sign_rule=SIGN_BIT):
+    """Sign of both raw fp32 tensors, then the zero-padded convolution."""
+    return bconv2d_zeropad_signed(sign(x, sign_rule), sign(w, sign_rule), stride, pad)
 
 
 def bconv2d(x, w, stride=1, pad=0, sign_rule=SIGN_BIT):

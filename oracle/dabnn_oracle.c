@@ -173,6 +173,49 @@ int oracle_bconv2d_at(const float *A, const float *Wt, const int32_t *idx, int64
 }
 
 /*
+ * The same convolution with ZERO padding, as the standard ONNX Convolution operator defines it
+ * (the paper builds its binary convolution on the ONNX Sign and Convolution operators: Table 1
+ * caption and Sec. 3): a tap outside the image contributes nothing, so border outputs are sums
+ * over fewer than K products and need not share K's parity.  Inside the image A is +-1.0f.
+ */
+int oracle_bconv2d_zeropad(const float *A, const float *Wt, int32_t *Y, int N, int H, int W,
+                           int Cin, int Cout, int kh, int kw, int stride, int pad)
+{
+    if (!A || !Wt || !Y || N <= 0 || Cin <= 0 || Cout <= 0)
+        return ORACLE_BAD_ARG;
+    const int Ho = out_dim(H, kh, stride, pad);
+    const int Wo = out_dim(W, kw, stride, pad);
+    if (Ho <= 0 || Wo <= 0 || (int64_t)kh * kw * Cin >= ((int64_t)1 << 24))
+        return ORACLE_BAD_ARG;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int ho = 0; ho < Ho; ++ho) {
+            for (int wo = 0; wo < Wo; ++wo) {
+                for (int co = 0; co < Cout; ++co) {
+                    float acc = 0.0f;
+                    for (int i = 0; i < kh; ++i) {
+                        const int hi = ho * stride - pad + i;
+                        if (hi < 0 || hi >= H)
+                            continue;
+                        for (int j = 0; j < kw; ++j) {
+                            const int wi = wo * stride - pad + j;
+                            if (wi < 0 || wi >= W)
+                                continue;
+                            const float *arow = A + (((int64_t)n * H + hi) * W + wi) * Cin;
+                            const float *wrow = Wt + (((int64_t)co * kh + i) * kw + j) * Cin;
+                            for (int c = 0; c < Cin; ++c)
+                                acc += arow[c] * wrow[c];
+                        }
+                    }
+                    Y[(((int64_t)n * Ho + ho) * Wo + wo) * Cout + co] = (int32_t)acc;
+                }
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Binary convolution fused with batch-norm and binarization (Sec. 2.1.1, last sentence: the
  * packing scheme is compatible with a fused BN-binarization layer).  Reading taken: the layer is
  * sign(BN(conv)), with inference-time batch-norm per output channel evaluated in fp64,

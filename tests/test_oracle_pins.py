@@ -340,3 +340,71 @@ def test_bnsign_closed_forms(oracle):
     assert not oracle.bconv2d_bnsign(x, wf, one, big, zero, one, 0.0, s, p).any()
     allneg = oracle.bconv2d_bnsign(x, wf, one, -big, zero, one, 0.0, s, p)
     assert np.all(allneg[..., 0] == np.uint64(0xFFFFFFFFFFFFFFFF)) and np.all(allneg[..., 1] == np.uint64(3))
+
+
+# ---- zero-padded variant (ONNX Convolution semantics; Table 1 caption, Sec. 3) -----------------
+
+def _valid_taps(H, W, k, s, p, ho, wo):
+    return [(i, j) for i in range(k) for j in range(k)
+            if 0 <= ho * s - p + i < H and 0 <= wo * s - p + j < W]
+
+
+@pytest.mark.parametrize("shape", SHAPES + [(2, 14, 14, 64, 16, 3, 1, 1), (1, 14, 14, 128, 8, 3, 2, 1)])
+def test_zeropad_against_torch_cpu_conv2d(oracle, shape):
+    """Library routine: torch's conv2d pads with zeros by definition."""
+    N, H, W, Cin, Cout, k, s, p = shape
+    A = oracle.sign(wl.activations((N, H, W, Cin), 61))
+    Wt = wl.weights((Cout, k, k, Cin), 62, p_plus=0.3)
+    y = oracle.bconv2d_zeropad_signed(A, Wt, s, p)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(A).permute(0, 3, 1, 2).double(),
+                                     torch.from_numpy(Wt).permute(0, 3, 1, 2).double(),
+                                     stride=s, padding=p).permute(0, 2, 3, 1)
+    assert y.dtype == np.int32
+    assert np.array_equal(y, ref.numpy().astype(np.int32))
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_zeropad_closed_forms_and_relation_to_plus_one_padding(oracle, shape):
+    N, H, W, Cin, Cout, k, s, p = shape
+    ones_a = np.ones((N, H, W, Cin), np.float32)
+    ones_w = np.ones((Cout, k, k, Cin), np.float32)
+    A = oracle.sign(wl.activations((N, H, W, Cin), 63))
+    Wt = wl.weights((Cout, k, k, Cin), 64, p_plus=0.3)
+    y1 = oracle.bconv2d_zeropad_signed(ones_a, ones_w, s, p)
+    y0 = oracle.bconv2d_zeropad_signed(A, Wt, s, p)
+    yp = oracle.bconv2d_signed(A, Wt, s, p)
+    Ho, Wo = y0.shape[1:3]
+    for ho in range(Ho):
+        for wo in range(Wo):
+            taps = _valid_taps(H, W, k, s, p, ho, wo)
+            # all +1: the output counts the taps inside the image
+            assert np.all(y1[:, ho, wo, :] == len(taps) * Cin)
+            # bounded by, and of the parity of, the number of products actually summed
+            assert np.all(np.abs(y0[:, ho, wo, :]) <= len(taps) * Cin)
+            assert np.all((y0[:, ho, wo, :] - len(taps) * Cin) % 2 == 0)
+            # +1 padding adds the plain sum of the weights under every outside tap
+            outside = [(i, j) for i in range(k) for j in range(k) if (i, j) not in taps]
+            extra = sum(Wt[:, i, j, :].sum(axis=-1) for i, j in outside) if outside else 0
+            assert np.array_equal(yp[:, ho, wo, :] - y0[:, ho, wo, :],
+                                  np.broadcast_to(np.asarray(extra, np.int64), (N, Cout)))
+    if p == 0:
+        assert np.array_equal(y0, yp)
+    assert np.array_equal(oracle.bconv2d_zeropad_signed(A, -Wt, s, p), -y0)
+
+
+@pytest.mark.parametrize("H,W,Cin,k,s,p", [(2, 2, 2, 3, 1, 1), (3, 3, 1, 3, 2, 1), (3, 2, 1, 3, 1, 2)])
+def test_zeropad_brute_force_all_activation_patterns(oracle, H, W, Cin, k, s, p):
+    """Every activation sign pattern against a definition over Python ints."""
+    Cout = 2
+    Wt = wl.weights((Cout, k, k, Cin), 65)
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    for bits in range(1 << (H * W * Cin)):
+        a = np.array([1.0 if (bits >> t) & 1 else -1.0 for t in range(H * W * Cin)],
+                     np.float32).reshape(1, H, W, Cin)
+        y = oracle.bconv2d_zeropad_signed(a, Wt, s, p)
+        for ho, wo, co in itertools.product(range(Ho), range(Wo), range(Cout)):
+            acc = 0
+            for i, j in _valid_taps(H, W, k, s, p, ho, wo):
+                for c in range(Cin):
+                    acc += int(a[0, ho * s - p + i, wo * s - p + j, c]) * int(Wt[co, i, j, c])
+            assert y[0, ho, wo, co] == acc
