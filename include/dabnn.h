@@ -99,6 +99,21 @@ int dabnn_bconv2d_algo(const uint64_t *a, const uint64_t *w, int32_t *y, int N, 
                        void *stream);
 
 /*
+ * Binary convolution with ZERO padding.  The paper builds its binary convolution on the standard
+ * ONNX Sign and Convolution operators (Table 1 caption, Sec. 3), and ONNX Convolution pads with 0:
+ * a tap outside the image contributes nothing, where dabnn_bconv2d counts it as +1 in every
+ * channel.  Same arguments, layouts and constraints as dabnn_bconv2d;
+ *
+ *   y0[n,ho,wo,co] = sum over taps INSIDE the image of (Cin - 2 * popcount(a XOR w)),
+ *
+ * which equals dabnn_bconv2d's y minus (Cin - 2*popcount(w[co,i,j,:])) for every outside tap.
+ * Interior outputs are identical; border outputs need not share K's parity.  Enqueues the
+ * convolution and, for pad > 0, one in-place pass over the border outputs on the same stream.
+ */
+int dabnn_bconv2d_zeropad(const uint64_t *a, const uint64_t *w, int32_t *y, int N, int H, int W,
+                          int Cin, int Cout, int kh, int kw, int stride, int pad, void *stream);
+
+/*
  * Binary convolution fused with batch-norm and binarization: the output is the NEXT layer's packed
  * activation tensor, so neither the int32 feature map nor a separate bit-pack pass exists.  The
  * paper notes that its packing is compatible with a fused BN-binarization layer (Sec. 2.1.1, last

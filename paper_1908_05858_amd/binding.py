@@ -39,6 +39,7 @@ def load():
     lib.dabnn_pack_weights.argtypes, lib.dabnn_pack_weights.restype = [vp, vp] + [i32] * 5 + [vp], i32
     lib.dabnn_bconv2d.argtypes, lib.dabnn_bconv2d.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
+    lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
     lib.dabnn_bconv2d_bnsign.argtypes, lib.dabnn_bconv2d_bnsign.restype = [vp] * 5 + [i32] * 9 + [vp], i32
@@ -50,7 +51,7 @@ def load():
 
 EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
-           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds"]
+           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad"]
 
 
 def status_string(status):
@@ -122,6 +123,23 @@ def bconv2d(a, w, Cin, stride=1, pad=0, out=None, algo=ALGO_AUTO):
     else:
         rc = load().dabnn_bconv2d_algo(*args, algo, _stream())
     _check(rc, "dabnn_bconv2d")
+    return out
+
+
+def bconv2d_zeropad(a, w, Cin, stride=1, pad=0, out=None):
+    """As bconv2d, with the zero padding of ONNX Convolution (outside taps contribute nothing)."""
+    N, H, W, Cw = a.shape
+    Cout, kh, kw, Cw2 = w.shape
+    if Cw != Cw2 or Cw != (Cin + 63) // 64:
+        raise ValueError("packed word counts do not match Cin")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_zeropad")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, Cout), dtype=torch.int32, device=a.device)
+    _check(load().dabnn_bconv2d_zeropad(_dev(a, torch.int64, "a"), _dev(w, torch.int64, "w"),
+                                        _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, kh, kw,
+                                        stride, pad, _stream()), "dabnn_bconv2d_zeropad")
     return out
 
 

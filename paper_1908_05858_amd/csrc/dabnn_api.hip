@@ -143,6 +143,19 @@ int dabnn_bconv2d(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H
                               stream);
 }
 
+int dabnn_bconv2d_zeropad(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H, int W,
+                          int Cin, int Cout, int kh, int kw, int stride, int pad, void* stream)
+{
+    const int rc = dabnn_bconv2d_algo(a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad,
+                                      DABNN_ALGO_AUTO, stream);
+    if (rc != DABNN_OK || pad == 0)
+        return rc;
+    dabnn::ConvShape s;
+    make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);  // validated by the call above
+    const hipError_t e = dabnn::launch_bconv_zeropad_fix(w, y, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
 int dabnn_bconv2d_bnsign(const uint64_t* a, const uint64_t* w, const int32_t* thr,
                          const uint64_t* flip, uint64_t* out, int N, int H, int W, int Cin,
                          int Cout, int kh, int kw, int stride, int pad, void* stream)

@@ -31,6 +31,10 @@ hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const 
 hipError_t launch_bconv_bnsign_reference(const uint64_t* a, const uint64_t* w, const int32_t* thr,
                                          const uint64_t* flip, uint64_t* out, const ConvShape& s,
                                          hipStream_t stream);
+// In-place correction of a finished +1-padded convolution output to zero padding (border pixels
+// only).  Any shape.
+hipError_t launch_bconv_zeropad_fix(const uint64_t* w, int32_t* y, const ConvShape& s,
+                                    hipStream_t stream);
 bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);

@@ -131,3 +131,12 @@ def test_bnsign_bad_arguments(lib):
     assert lib.dabnn_bconv2d_bnsign(a, w, t, f, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
     assert lib.dabnn_bconv2d_bnsign(a, w, t, f, o, 1, 4, 4, 64, 0, 3, 3, 1, 1, None) == 2
     assert lib.dabnn_bconv2d_bnsign(a, w, t, P(0x40004), o, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
+
+
+def test_zeropad_bad_arguments(lib):
+    P = ctypes.c_void_p
+    a, w, y = P(0x10000), P(0x20000), P(0x30000)
+    assert lib.dabnn_bconv2d_zeropad(a, w, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d_zeropad(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2   # pad >= k
+    assert lib.dabnn_bconv2d_zeropad(a, w, y, 1, 4, 4, 64, 64, 3, 3, 0, 1, None) == 2   # stride 0
+    assert lib.dabnn_bconv2d_zeropad(a, w, P(0x30002), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3

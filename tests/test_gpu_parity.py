@@ -183,6 +183,52 @@ def test_kernel_variants(dabnn, oracle, env, monkeypatch):
         run_conv(dabnn, oracle, *shape, seed=31337 + sum(shape), algo=algo)
 
 
+# ------------------------------------------------------------------- zero padding (ONNX Convolution)
+
+ZEROPAD_SHAPES = ODD_SHAPES + [
+    (2, 14, 14, 64, 64, 3, 1, 1),
+    (3, 28, 28, 128, 128, 3, 2, 1),
+    (2, 7, 7, 512, 512, 3, 1, 1),
+    (4, 56, 56, 64, 64, 3, 1, 1),
+    (1, 1, 1, 64, 8, 3, 1, 1),       # every tap but the centre is outside
+    (2, 2, 9, 64, 8, 5, 1, 2),       # rows that are outside at the top and at the bottom at once
+    (1, 5, 5, 70, 6, 3, 4, 2),       # stride larger than the pad
+]
+
+
+@pytest.mark.parametrize("shape", ZEROPAD_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_bconv2d_zeropad(dabnn, oracle, shape):
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("zeropad", shape, flush=True)
+    x = wl.activations((N, H, W, Cin), 777 + sum(shape))
+    wf = wl.weights((Cout, k, k, Cin), 778 + sum(shape), p_plus=0.3)
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    y = dabnn.bconv2d_zeropad(a, wp, Cin, stride, pad)
+    want = oracle.bconv2d_zeropad(x, wf, stride, pad)
+    assert y.dtype == torch.int32 and tuple(y.shape) == want.shape
+    assert np.array_equal(y.cpu().numpy(), want)
+
+
+def test_bconv2d_zeropad_full_batch_layer(dabnn, oracle):
+    """Batch 256 at a benchmark shape: three whole images against the oracle, and, at any size,
+    the interior equals the +1-padded result while the border differs by an image-independent
+    amount."""
+    L = wl.BIREAL18_BODY[0]
+    N = wl.CFG5_BATCH
+    x = wl.activations((N, L.H, L.W, L.Cin), wl.seed_for(5, 100))
+    wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, 0))
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    y0 = dabnn.bconv2d_zeropad(a, wp, L.Cin, L.stride, 1).cpu().numpy()
+    y1 = dabnn.bconv2d(a, wp, L.Cin, L.stride, 1).cpu().numpy()
+    for n in (0, N // 2, N - 1):
+        assert np.array_equal(y0[n:n + 1], oracle.bconv2d_zeropad(x[n:n + 1], wf, L.stride, 1))
+    d = y1 - y0
+    assert not d[:, 1:-1, 1:-1, :].any()
+    assert np.array_equal(d, np.broadcast_to(d[:1], d.shape))
+
+
 # ------------------------------------------------------------------------------- fused BN + sign
 
 def _bn_params(C, seed):
