@@ -7,7 +7,9 @@ package.  It imports nothing from the GPU package and the GPU package imports no
 What each function computes, with the passage it follows, is stated in ``dabnn_oracle.c``:
 ``sign`` / ``bitpack`` follow Sec. 2.1.1; ``bconv2d`` is the +-1 float cross-correlation that
 Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal (``bconv2d_zeropad``: the same with the zero padding
-of the ONNX Convolution operator the paper builds on); ``bconv2d_bnsign`` is that convolution followed by
+of the ONNX Convolution operator the paper builds on); ``bgemm_signed`` is Eq. 1 and the dot
+product it stands for, ``im2col_signed`` the patch matrix that turns a convolution into that
+BGEMM (Fig. 4's comparison route); ``bconv2d_bnsign`` is that convolution followed by
 fp64 batch-norm and the sign (fused BN-binarization, Sec. 2.1.1); ``glue`` only generates inputs.
 
 Every function here is pinned by ``tests/test_oracle_pins.py`` (closed forms, invariants, brute
@@ -50,12 +52,13 @@ def _load():
     lib.oracle_conv_out_dim.argtypes = [i32] * 4
     lib.oracle_bconv2d.argtypes = [vp, vp, vp] + [i32] * 9
     lib.oracle_bconv2d_zeropad.argtypes = [vp, vp, vp] + [i32] * 9
+    lib.oracle_bgemm.argtypes = [vp, vp, vp, i64, i32, i32, i32]
     lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
     lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
     lib.oracle_bconv2d_bnsign.argtypes = [vp] * 6 + [ctypes.c_float, vp] + [i32] * 9
     for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
               lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign,
-              lib.oracle_bconv2d_zeropad):
+              lib.oracle_bconv2d_zeropad, lib.oracle_bgemm):
         f.restype = i32
     _lib = lib
     return lib
@@ -170,6 +173,41 @@ def bconv2d_bnsign(x, w, gamma, beta, mean, var, eps, stride=1, pad=0, sign_rule
                                          ctypes.c_float(eps), out.ctypes.data, N, H, W, Cin, Cout, kh,
                                          kw, stride, pad), "bconv2d_bnsign")
     return out
+
+
+BGEMM_SIGNED = 0   # sum_k A_ik * B_jk = 2*C_ij - K
+BGEMM_MATCHES = 1  # C_ij of Eq. 1: bitcount(xnor)
+
+
+def bgemm_signed(A, B, mode=BGEMM_SIGNED):
+    """BGEMM (Sec. 2.1.2, Eq. 1) on +-1.0f operands A [M,K], B [N,K] -> int32 [M,N]."""
+    A, B = _f32(A), _f32(B)
+    M, K = A.shape
+    N, K2 = B.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ")
+    C = np.empty((M, N), dtype=np.int32)
+    _check(_load().oracle_bgemm(A.ctypes.data, B.ctypes.data, C.ctypes.data, M, N, K, mode), "bgemm")
+    return C
+
+
+def im2col_signed(A, kh, kw, stride=1, pad=0):
+    """Patch matrix of a +-1.0f NHWC tensor: [N*Ho*Wo, kh*kw, Cin], taps in (i, j) order,
+    out-of-image taps +1.0 -- the matrix whose BGEMM with the [Cout, kh*kw*Cin] filter matrix is
+    the convolution (the BGEMM route the paper compares its direct convolution with, Fig. 4)."""
+    A = _f32(A)
+    N, H, W, Cin = A.shape
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    padded = np.ones((N, H + 2 * pad, W + 2 * pad, Cin), np.float32)
+    padded[:, pad:pad + H, pad:pad + W, :] = A
+    cols = np.empty((N, Ho, Wo, kh * kw, Cin), np.float32)
+    for i in range(kh):
+        for j in range(kw):
+            cols[:, :, :, i * kw + j, :] = padded[:, i:i + (Ho - 1) * stride + 1:stride,
+                                                  j:j + (Wo - 1) * stride + 1:stride, :]
+    return cols.reshape(N * Ho * Wo, kh * kw, Cin)
 
 
 def glue(x, y, gamma, beta, K, stride):

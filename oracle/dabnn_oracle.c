@@ -216,6 +216,40 @@ int oracle_bconv2d_zeropad(const float *A, const float *Wt, int32_t *Y, int N, i
 }
 
 /*
+ * BGEMM (Sec. 2.1.2, Eq. 1) on already-binarized operands.
+ *   A : [M][K] values +-1.0f          (row i is the paper's A_{i,.})
+ *   B : [N][K] values +-1.0f          (row j is the paper's column B_{.,j})
+ *   C : [M][N] int32
+ * mode 1 is Eq. 1 as printed: C_ij = number of positions where the two vectors agree, i.e.
+ * bitcount(xnor) over the K real bits.  mode 0 is the +-1 dot product that count stands for,
+ * sum_k A_ik * B_jk = 2*C_ij - K, the quantity the convolution entry points return.
+ */
+int oracle_bgemm(const float *A, const float *B, int32_t *C, int64_t M, int N, int K, int mode)
+{
+    if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0 || K >= (1 << 24) || (mode != 0 && mode != 1))
+        return ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        const float *a = A + i * K;
+        for (int j = 0; j < N; ++j) {
+            const float *b = B + (int64_t)j * K;
+            if (mode == 1) {
+                int32_t agree = 0;
+                for (int k = 0; k < K; ++k)
+                    agree += (a[k] == b[k]);
+                C[i * N + j] = agree;
+            } else {
+                float acc = 0.0f;
+                for (int k = 0; k < K; ++k)
+                    acc += a[k] * b[k];
+                C[i * N + j] = (int32_t)acc;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Binary convolution fused with batch-norm and binarization (Sec. 2.1.1, last sentence: the
  * packing scheme is compatible with a fused BN-binarization layer).  Reading taken: the layer is
  * sign(BN(conv)), with inference-time batch-norm per output channel evaluated in fp64,

@@ -408,3 +408,64 @@ def test_zeropad_brute_force_all_activation_patterns(oracle, H, W, Cin, k, s, p)
                 for c in range(Cin):
                     acc += int(a[0, ho * s - p + i, wo * s - p + j, c]) * int(Wt[co, i, j, c])
             assert y[0, ho, wo, co] == acc
+
+
+# ---- BGEMM (Sec. 2.1.2, Eq. 1) and the patch matrix ---------------------------------------------
+
+BGEMM_SHAPES = [(1, 1, 1), (3, 5, 7), (17, 9, 64), (8, 33, 100), (70, 16, 576), (5, 4, 1300)]
+
+
+@pytest.mark.parametrize("M,N,K", BGEMM_SHAPES)
+def test_bgemm_against_numpy_matmul_and_popcount(oracle, M, N, K):
+    A = oracle.sign(wl.activations((M, K), 71 + M))
+    B = wl.weights((N, K), 72 + N, p_plus=0.4)
+    dot = oracle.bgemm_signed(A, B, oracle.BGEMM_SIGNED)
+    cnt = oracle.bgemm_signed(A, B, oracle.BGEMM_MATCHES)
+    # library routine, fp64
+    assert np.array_equal(dot, (A.astype(np.float64) @ B.astype(np.float64).T).astype(np.int32))
+    # Eq. 1 on packed words with Python integers: bitcount(xnor) over the K real bits
+    mask = (1 << K) - 1
+    abits = [int("".join("1" if v < 0 else "0" for v in row[::-1]), 2) for row in A]
+    bbits = [int("".join("1" if v < 0 else "0" for v in row[::-1]), 2) for row in B]
+    for i in range(M):
+        for j in range(N):
+            assert cnt[i, j] == bin(~(abits[i] ^ bbits[j]) & mask).count("1")
+    assert np.array_equal(dot, 2 * cnt - K)
+    assert cnt.min() >= 0 and cnt.max() <= K
+
+
+def test_bgemm_closed_forms(oracle):
+    M, N, K = 6, 5, 130
+    A = oracle.sign(wl.activations((M, K), 73))
+    assert np.all(np.diag(oracle.bgemm_signed(A, A)) == K)
+    assert np.all(np.diag(oracle.bgemm_signed(A, A, oracle.BGEMM_MATCHES)) == K)
+    assert np.all(np.diag(oracle.bgemm_signed(A, -A)) == -K)
+    assert np.all(np.diag(oracle.bgemm_signed(A, -A, oracle.BGEMM_MATCHES)) == 0)
+    B = wl.weights((N, K), 74)
+    assert np.array_equal(oracle.bgemm_signed(A, B).T, oracle.bgemm_signed(B, A))
+    # a single flipped position changes exactly one row of the dot products by 2 * b_jk
+    A2 = A.copy()
+    A2[2, 17] = -A2[2, 17]
+    d = oracle.bgemm_signed(A2, B) - oracle.bgemm_signed(A, B)
+    assert not d[[0, 1, 3, 4, 5]].any() and np.array_equal(d[2], (2 * A2[2, 17] * B[:, 17]).astype(np.int32))
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_im2col_bgemm_equals_direct_convolution(oracle, shape):
+    """The patch matrix times the filter matrix is the (separately pinned) direct convolution;
+    its rows are checked element by element against the tensor as well."""
+    N, H, W, Cin, Cout, k, s, p = shape
+    A = oracle.sign(wl.activations((N, H, W, Cin), 75))
+    Wt = wl.weights((Cout, k, k, Cin), 76, p_plus=0.3)
+    cols = oracle.im2col_signed(A, k, k, s, p)
+    y = oracle.bconv2d_signed(A, Wt, s, p)
+    Ho, Wo = y.shape[1:3]
+    assert cols.shape == (N * Ho * Wo, k * k, Cin)
+    for n, ho, wo in itertools.product(range(N), range(Ho), range(Wo)):
+        row = cols[(n * Ho + ho) * Wo + wo]
+        for i, j in itertools.product(range(k), range(k)):
+            hi, wi = ho * s - p + i, wo * s - p + j
+            want = A[n, hi, wi] if (0 <= hi < H and 0 <= wi < W) else np.ones(Cin, np.float32)
+            assert np.array_equal(row[i * k + j], want)
+    g = oracle.bgemm_signed(cols.reshape(cols.shape[0], -1), Wt.reshape(Cout, -1))
+    assert np.array_equal(g.reshape(y.shape), y)
