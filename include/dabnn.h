@@ -46,10 +46,18 @@ typedef enum {
     DABNN_ALGO_REFERENCE = 1, /* one thread per output, any shape; the GPU-side safety net */
     DABNN_ALGO_WREG = 2,      /* weights resident in VGPRs, activations broadcast through SGPRs;
                                  3x3 kernels with ceil(Cin/64) in {1,2,4,8}, stride 1 or 2 */
-    DABNN_ALGO_AREG = 3       /* each lane keeps one output pixel's 3x3 window in VGPRs, weights are
+    DABNN_ALGO_AREG = 3,      /* each lane keeps one output pixel's 3x3 window in VGPRs, weights are
                                  broadcast through SGPRs; 3x3 kernels with ceil(Cin/64) in
                                  {1,2,4,8}, stride 1 or 2, Cout % 4 == 0 (8 for Cin <= 64), y 16-byte aligned */
+    DABNN_ALGO_BGEMM = 4      /* 1x1, stride 1, pad 0 only: the convolution IS the BGEMM of Eq. 1;
+                                 Cout % 16 == 0, y 16-byte aligned, row lengths dabnn_bgemm's
+                                 fast kernel supports */
 } dabnn_algo;
+
+typedef enum {
+    DABNN_BGEMM_SIGNED = 0,  /* sum_k A_ik * B_jk over +-1 values = 2*C_ij - K (what the convolutions return) */
+    DABNN_BGEMM_MATCHES = 1  /* C_ij of Eq. 1 as printed: bitcount(xnor), the number of agreeing bits */
+} dabnn_bgemm_mode;
 
 /* ceil(C / 64): 64-bit words per pixel for C channels.  Returns -1 if C <= 0. */
 int64_t dabnn_packed_words(int64_t C);
@@ -97,6 +105,36 @@ int dabnn_bconv2d(const uint64_t *a, const uint64_t *w, int32_t *y, int N, int H
 int dabnn_bconv2d_algo(const uint64_t *a, const uint64_t *w, int32_t *y, int N, int H, int W,
                        int Cin, int Cout, int kh, int kw, int stride, int pad, int algo,
                        void *stream);
+
+/*
+ * BGEMM (Sec. 2.1.2, Eq. 1) on bit-packed matrices:
+ *
+ *   DABNN_BGEMM_MATCHES:  C[i][j] = sum_q bitcount(xnor(A[i][q], B[j][q])) restricted to the K real bits
+ *                                 = K - sum_q popcount(A[i][q] XOR B[j][q])
+ *   DABNN_BGEMM_SIGNED :  C[i][j] = K - 2 * sum_q popcount(A[i][q] XOR B[j][q])
+ *
+ *   A : u64 [M][Kw]  device, row-major; row i is the paper's A_{i,.}
+ *   B : u64 [N][Kw]  device, row-major; row j is the paper's column B_{.,j}
+ *   C : i32 [M][N]   device, written completely
+ * Of the 64*Kw bits of a row the first K (0 < K <= 64*Kw, K < 2^23) are real; every other bit must
+ * be 0 in both operands.  Kw need not be ceil(K/64): a patch-matrix row has kh*kw*ceil(Cin/64)
+ * words holding kh*kw*Cin real bits.  Any shape runs; the fast kernel needs N % 16 == 0, C
+ * 16-byte aligned and 2*Kw in {2,4,6,8,12,16,18,24,32,36,48,64,72,96,128,144}.
+ */
+int dabnn_bgemm(const uint64_t *A, const uint64_t *B, int32_t *C, int64_t M, int N, int Kw, int K,
+                int mode, void *stream);
+
+/*
+ * Patch matrix (im2col) of a packed NHWC tensor: row (n,ho,wo) holds the kh*kw taps under that
+ * output in (i, j) order, ceil(Cin/64) words each; a tap outside the image is an all-zero word
+ * (+1 in every channel).  dabnn_bgemm of it with the packed filters [Cout][kh*kw*ceil(Cin/64)],
+ * K = kh*kw*Cin, equals dabnn_bconv2d -- the BGEMM route that the paper measures its direct
+ * convolution against (Fig. 4).
+ *   a    : u64 [N][H][W][ceil(Cin/64)]                 device
+ *   cols : u64 [N*Ho*Wo][kh*kw*ceil(Cin/64)]           device, written completely (< 2^31 words)
+ */
+int dabnn_im2col(const uint64_t *a, uint64_t *cols, int N, int H, int W, int Cin, int kh, int kw,
+                 int stride, int pad, void *stream);
 
 /*
  * Binary convolution with ZERO padding.  The paper builds its binary convolution on the standard

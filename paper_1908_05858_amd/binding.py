@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdabnn.so")
 
 SIGN_BIT, SIGN_GE0 = 0, 1
-ALGO_AUTO, ALGO_REFERENCE, ALGO_WREG, ALGO_AREG = 0, 1, 2, 3
+ALGO_AUTO, ALGO_REFERENCE, ALGO_WREG, ALGO_AREG, ALGO_BGEMM = 0, 1, 2, 3, 4
 
 _lib = None
 
@@ -39,6 +39,8 @@ def load():
     lib.dabnn_pack_weights.argtypes, lib.dabnn_pack_weights.restype = [vp, vp] + [i32] * 5 + [vp], i32
     lib.dabnn_bconv2d.argtypes, lib.dabnn_bconv2d.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
+    lib.dabnn_bgemm.argtypes, lib.dabnn_bgemm.restype = [vp] * 3 + [i64, i32, i32, i32, i32, vp], i32
+    lib.dabnn_im2col.argtypes, lib.dabnn_im2col.restype = [vp] * 2 + [i32] * 8 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
@@ -51,7 +53,7 @@ def load():
 
 EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
-           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad"]
+           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col"]
 
 
 def status_string(status):
@@ -140,6 +142,37 @@ def bconv2d_zeropad(a, w, Cin, stride=1, pad=0, out=None):
     _check(load().dabnn_bconv2d_zeropad(_dev(a, torch.int64, "a"), _dev(w, torch.int64, "w"),
                                         _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, kh, kw,
                                         stride, pad, _stream()), "dabnn_bconv2d_zeropad")
+    return out
+
+
+BGEMM_SIGNED, BGEMM_MATCHES = 0, 1
+
+
+def bgemm(A, B, K, mode=BGEMM_SIGNED, out=None):
+    """A: int64 [M,Kw], B: int64 [N,Kw] (packed rows, K real bits) -> int32 [M,N] (Eq. 1)."""
+    M, Kw = A.shape
+    N, Kw2 = B.shape
+    if Kw != Kw2:
+        raise ValueError("row lengths differ")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(load().dabnn_bgemm(_dev(A, torch.int64, "A"), _dev(B, torch.int64, "B"),
+                              _dev(out, torch.int32, "out"), M, N, Kw, K, mode, _stream()), "dabnn_bgemm")
+    return out
+
+
+def im2col(a, Cin, kh, kw, stride=1, pad=0, out=None):
+    """a: int64 [N,H,W,Cw] -> patch matrix int64 [N*Ho*Wo, kh*kw*Cw] (outside taps zero words)."""
+    N, H, W, Cw = a.shape
+    if Cw != (Cin + 63) // 64:
+        raise ValueError("packed word count does not match Cin")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_im2col")
+    if out is None:
+        out = torch.empty((N * Ho * Wo, kh * kw * Cw), dtype=torch.int64, device=a.device)
+    _check(load().dabnn_im2col(_dev(a, torch.int64, "a"), _dev(out, torch.int64, "out"), N, H, W, Cin,
+                               kh, kw, stride, pad, _stream()), "dabnn_im2col")
     return out
 
 

@@ -1,0 +1,462 @@
+// Binary direct convolution (Sec. 2.1.2, Eq. 6-7), "activation-stationary" kernel family.
+//
+// Lane l of a wavefront owns one output pixel and keeps the 3x3xCin window under it (18*Cw
+// dwords, out-of-image taps as zero words) in VGPRs -- the paper's idea of holding the window
+// in registers while it is reused (Fig. 3), here reused across OUTPUT CHANNELS instead of across
+// neighbouring pixels.  The wavefront then walks over output channels: the packed filter words
+// are the same for all 64 lanes, so they are fetched with scalar loads and used as the SGPR
+// operand of v_xor_b32, followed by v_bcnt_u32_b32 which accumulates the popcount (Eq. 6).  Four
+// output channels are computed together (four independent accumulation chains).  All border
+// handling happens once per window load; the hot loop contains no address arithmetic, no masks
+// and no LDS.
+//
+// Stores: a lane holds consecutive channels of ONE pixel, so a direct store writes 16 bytes per
+// lane at a stride of Cout*4 bytes -- 64 partial cache lines per instruction, which saturates the
+// L2 write path long before HBM.  When Cout is a multiple of 16 the kernel therefore finishes 16
+// (or 32) channels, transposes the 64 x 16 tile through a wavefront-private slice of LDS and
+// stores it so that neighbouring lanes write the 64 (or 128) contiguous bytes of one pixel.
+//
+// This family suits layers with few words per pixel (small windows, small filters that stay in
+// the scalar cache); the filter-stationary family in bconv.hip suits the opposite case.
+#pragma once
+#include "kernel_util.h"
+#include "launch.h"
+
+namespace dabnn {
+namespace {
+
+// acc[q] += sum_{d<3} popcount(w[q][d] ^ a[d]) for four output channels q.  w sits in SGPRs
+// (written by scalar loads only: a VALU-written SGPR would need wait states the compiler cannot
+// see inside the assembly), a in VGPRs.  Four independent chains hide the VALU latency.
+template <bool FIRST>
+__device__ __forceinline__ void xor_popc_4x3(int* acc, const uint32_t* a, const uint32_t* w0,
+                                             const uint32_t* w1, const uint32_t* w2,
+                                             const uint32_t* w3)
+{
+    uint32_t t0, t1, t2, t3;
+#define DABNN_TAIL                                                                      \
+    "v_xor_b32 %4, %12, %9\n\t"                                                         \
+    "v_xor_b32 %5, %15, %9\n\t"                                                         \
+    "v_xor_b32 %6, %18, %9\n\t"                                                         \
+    "v_xor_b32 %7, %21, %9\n\t"                                                         \
+    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
+    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
+    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
+    "v_bcnt_u32_b32 %3, %7, %3\n\t"                                                     \
+    "v_xor_b32 %4, %13, %10\n\t"                                                        \
+    "v_xor_b32 %5, %16, %10\n\t"                                                        \
+    "v_xor_b32 %6, %19, %10\n\t"                                                        \
+    "v_xor_b32 %7, %22, %10\n\t"                                                        \
+    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
+    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
+    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
+    "v_bcnt_u32_b32 %3, %7, %3"
+#define DABNN_INPUTS                                                                          \
+    "v"(a[0]), "v"(a[1]), "v"(a[2]), "s"(w0[0]), "s"(w0[1]), "s"(w0[2]), "s"(w1[0]), "s"(w1[1]), \
+        "s"(w1[2]), "s"(w2[0]), "s"(w2[1]), "s"(w2[2]), "s"(w3[0]), "s"(w3[1]), "s"(w3[2])
+    if constexpr (FIRST) {
+        // the accumulators start here: the first popcounts add to the constant 0
+        asm("v_xor_b32 %4, %11, %8\n\t"
+            "v_xor_b32 %5, %14, %8\n\t"
+            "v_xor_b32 %6, %17, %8\n\t"
+            "v_xor_b32 %7, %20, %8\n\t"
+            "v_bcnt_u32_b32 %0, %4, 0\n\t"
+            "v_bcnt_u32_b32 %1, %5, 0\n\t"
+            "v_bcnt_u32_b32 %2, %6, 0\n\t"
+            "v_bcnt_u32_b32 %3, %7, 0\n\t" DABNN_TAIL
+            : "=&v"(acc[0]), "=&v"(acc[1]), "=&v"(acc[2]), "=&v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3)
+            : DABNN_INPUTS);
+    } else {
+        asm("v_xor_b32 %4, %11, %8\n\t"
+            "v_xor_b32 %5, %14, %8\n\t"
+            "v_xor_b32 %6, %17, %8\n\t"
+            "v_xor_b32 %7, %20, %8\n\t"
+            "v_bcnt_u32_b32 %0, %4, %0\n\t"
+            "v_bcnt_u32_b32 %1, %5, %1\n\t"
+            "v_bcnt_u32_b32 %2, %6, %2\n\t"
+            "v_bcnt_u32_b32 %3, %7, %3\n\t" DABNN_TAIL
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3)
+            : DABNN_INPUTS);
+    }
+#undef DABNN_TAIL
+#undef DABNN_INPUTS
+}
+
+// y = K - 2 * diff as one v_mad_i32_i24 (diff <= K < 2^23).  K is a kernel argument, so the SGPR
+// it sits in is written by a scalar load.
+__device__ __forceinline__ int finish_output(int diff, int K)
+{
+    int y;
+    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(y) : "v"(diff), "s"(K));
+    return y;
+}
+
+// Outputs are written once and never read by this kernel.  The transposed path stores whole
+// 64- or 128-byte runs, so it stores non-temporally (streaming through L2); the direct path
+// writes 16-byte pieces of a line at different times and leaves it to L2 to merge them.
+typedef int v4i __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ void store_out4(void* dst, const int4& o)
+{
+    v4i v = {o.x, o.y, o.z, o.w};
+    if constexpr (STREAM)
+        __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
+    else
+        *reinterpret_cast<v4i*>(dst) = v;
+}
+
+// Fused threshold: bits = (bits << 1) | (y < thr) for one output channel, with y = K - 2d (d the
+// popcount sum) and kt = K - thr:  y < thr  <=>  kt - 2d < 0.  Plain VALU arithmetic: the sign bit
+// of kt - 2d is shifted in with v_alignbit_b32, no lane mask ever goes through an SGPR pair.
+__device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
+{
+    const int t = kt - 2 * d;  // |kt|, 2d < 2^31: no overflow
+    bits = __builtin_amdgcn_alignbit(bits, static_cast<uint32_t>(t), 31);
+}
+
+// Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
+// and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
+// (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
+//   TR = 16 or 32 (transposed store through LDS): CG = TR.   TR = 0, direct 16-byte stores:
+//   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
+//   an output word).
+constexpr int kBits = -1;
+constexpr int kDC = 6;
+template <int CW, int TR>
+struct AregGeom {
+    static constexpr int D = 2 * CW;
+    static constexpr int KD = 18 * CW;
+    static constexpr int CG = TR > 0 ? TR : (TR == kBits ? 16 : (CW == 1 ? 8 : 4));
+    static constexpr int CHUNKS = KD / kDC;            // units per quad
+    static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
+    static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
+};
+
+// Scalar loads of unit UNIT of the group starting at output channel cout0.
+template <int CW, int TR, int UNIT, int SB>
+__device__ __forceinline__ void areg_load_unit(uint32_t (&sb)[SB], const uint32_t* __restrict__ w,
+                                               int cout0)
+{
+    using G = AregGeom<CW, TR>;
+    constexpr int quad = UNIT / G::CHUNKS;
+    constexpr int chunk = UNIT % G::CHUNKS;
+    const uint32_t* src = w + static_cast<size_t>(cout0 + 4 * quad) * G::KD + chunk * kDC;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int d = 0; d < kDC; ++d)
+            sb[q * kDC + d] = src[q * G::KD + d];
+    }
+}
+
+template <int CW, int TR, int UNIT, int SB, int KD, int CG>
+__device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int (&acc)[CG],
+                                                  const uint32_t (&areg)[KD])
+{
+    using G = AregGeom<CW, TR>;
+    constexpr int quad = UNIT / G::CHUNKS;
+    constexpr int chunk = UNIT % G::CHUNKS;
+    // the quad's accumulators are born in its first block: no zero-initialisation needed
+    xor_popc_4x3<chunk == 0>(&acc[4 * quad], &areg[chunk * kDC], &sb[0 * kDC], &sb[1 * kDC],
+                             &sb[2 * kDC], &sb[3 * kDC]);
+    xor_popc_4x3<false>(&acc[4 * quad], &areg[chunk * kDC + 3], &sb[0 * kDC + 3], &sb[1 * kDC + 3],
+                        &sb[2 * kDC + 3], &sb[3 * kDC + 3]);
+}
+
+template <int CW, int S, int TR>
+__global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
+    const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
+    int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
+    int n_ranges, int base_groups, int rem_groups, const int32_t* __restrict__ thr,
+    const uint2* __restrict__ flip)
+{
+    using G = AregGeom<CW, TR>;
+    // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
+    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : 4];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= n_ranges)
+        return;  // the grid is rounded up to whole workgroups
+    // balanced contiguous partition of (tile, channel group) pairs, channel group fastest
+    int g = gw * base_groups + (gw < rem_groups ? gw : rem_groups);
+    const int g_begin = g;
+    const int g_end = g + base_groups + (gw < rem_groups ? 1 : 0);
+    if (g >= g_end)
+        return;
+    int tile = g / groups_per_tile;
+    int cgi = g - tile * groups_per_tile;
+
+    uint32_t areg[G::KD];
+    bool pvalid = false;
+    uint32_t ybase = 0;
+    // The 3x3xCw window under this lane's output pixel; taps outside the image become zero
+    // words (every channel +1).
+    auto load_window = [&](int t) {
+        const int p = t * 64 + lane;
+        pvalid = p < total_pix;
+        const int pc = pvalid ? p : total_pix - 1;
+        const int n = pc / (Ho * Wo);
+        const int r = pc - n * (Ho * Wo);
+        const int ho = r / Wo;
+        const int wo = r - ho * Wo;
+        ybase = static_cast<uint32_t>(pc) * static_cast<uint32_t>(Cout);
+        // Pixel index of the window's top-left tap; taps are addressed as a uniform base plus a
+        // 32-bit byte offset (the launcher checks that the tensor fits), invalid taps read
+        // offset 0 and are masked.
+        const int hi0 = ho * S - pad, wi0 = wo * S - pad;
+        const int top_left = (n * H + hi0) * W + wi0;
+        const char* base = reinterpret_cast<const char*>(a);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const bool rv = static_cast<unsigned>(hi0 + i) < static_cast<unsigned>(H);
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const bool v = rv && static_cast<unsigned>(wi0 + j) < static_cast<unsigned>(W);
+                const uint32_t keep = v ? 0xffffffffu : 0u;
+                const uint32_t off =
+                    v ? static_cast<uint32_t>(top_left + i * W + j) * (G::D * 4u) : 0u;
+                const char* src = base + off;
+                if constexpr (G::D == 2) {
+                    const uint2 u = *reinterpret_cast<const uint2*>(src);
+                    areg[(i * 3 + j) * 2 + 0] = u.x & keep;
+                    areg[(i * 3 + j) * 2 + 1] = u.y & keep;
+                } else {
+#pragma unroll
+                    for (int d = 0; d < G::D; d += 4) {
+                        const uint4 u = *reinterpret_cast<const uint4*>(src + d * 4);
+                        areg[(i * 3 + j) * G::D + d + 0] = u.x & keep;
+                        areg[(i * 3 + j) * G::D + d + 1] = u.y & keep;
+                        areg[(i * 3 + j) * G::D + d + 2] = u.z & keep;
+                        areg[(i * 3 + j) * G::D + d + 3] = u.w & keep;
+                    }
+                }
+            }
+        }
+    };
+    load_window(tile);
+
+    uint32_t sb0[G::SB], sb1[G::SB];
+    areg_load_unit<CW, TR, 0>(sb0, w, cgi * G::CG);
+    uint32_t bits32 = 0;  // fused bit-pack output under construction
+
+    for (; g < g_end; ++g) {
+        int ncgi = cgi + 1, ntile = tile;
+        if (ncgi == groups_per_tile) {
+            ncgi = 0;
+            ++ntile;
+        }
+
+        int acc[G::CG];
+        // The group's 16 thresholds, fetched with vector loads at the start of the group (every
+        // lane reads the same 64 bytes) so that they neither occupy SGPRs nor disturb the
+        // scalar-load pipeline; they are first used after the last unit.
+        int thr_v[TR == kBits ? 16 : 1];
+        if constexpr (TR == kBits) {
+            uint32_t lane_off = 0;
+            asm volatile("" : "+v"(lane_off));  // keeps the address per-lane: a vector load
+            const int4* tp = reinterpret_cast<const int4*>(thr + cgi * 16 + lane_off);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int4 t = tp[q];
+                thr_v[4 * q + 0] = t.x;
+                thr_v[4 * q + 1] = t.y;
+                thr_v[4 * q + 2] = t.z;
+                thr_v[4 * q + 3] = t.w;
+            }
+        }
+
+        // Software pipeline: while unit u feeds the VALU, unit u+1 is in flight.
+        static_for<0, G::UNITS>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            wait_scalar_loads();
+            schedule_fence();
+            if constexpr (u + 1 < G::UNITS) {
+                if constexpr (u % 2 == 0)
+                    areg_load_unit<CW, TR, u + 1>(sb1, w, cgi * G::CG);
+                else
+                    areg_load_unit<CW, TR, u + 1>(sb0, w, cgi * G::CG);
+            } else {
+                if (g + 1 < g_end)  // first unit of the next group (UNITS is even: buffer 0)
+                    areg_load_unit<CW, TR, 0>(sb0, w, ncgi * G::CG);
+            }
+            schedule_fence();
+            if constexpr (u % 2 == 0)
+                areg_compute_unit<CW, TR, u>(sb0, acc, areg);
+            else
+                areg_compute_unit<CW, TR, u>(sb1, acc, areg);
+            schedule_fence();
+        });
+
+        if constexpr (TR == kBits) {
+            // Fused threshold + bit-pack: y < thr  <=>  (K - thr) - 2d < 0.  The 16 channels are
+            // shifted in in ascending order and bit-reversed into place afterwards.  An even
+            // group whose odd partner belongs to this wavefront too is held back, and the pair
+            // leaves as one 32-bit store; a group whose partner belongs to a neighbouring
+            // wavefront leaves as a 16-bit store (distinct bytes of the word: no race).
+            const bool odd = (cgi & 1) != 0;
+            if (!odd)
+                bits32 = 0;
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                shift_in(bits32, acc[q], K - thr_v[q]);
+            const uint2 fl = flip[cgi >> 2];
+            const uint32_t fl32 = (cgi & 2) ? fl.y : fl.x;
+            const size_t half_index =
+                static_cast<size_t>(tile * 64 + lane) * (groups_per_tile >> 1) + (cgi >> 1);
+            const uint32_t rev = __builtin_bitreverse32(bits32);
+            if (odd && g > g_begin) {
+                if (pvalid)
+                    reinterpret_cast<uint32_t*>(y)[half_index] = rev ^ fl32;
+            } else if (odd || g + 1 >= g_end) {
+                const uint32_t fl16 = odd ? (fl32 >> 16) : (fl32 & 0xffffu);
+                if (pvalid)
+                    reinterpret_cast<uint16_t*>(y)[2 * half_index + (odd ? 1 : 0)] =
+                        static_cast<uint16_t>((rev >> 16) ^ fl16);
+            }
+        } else if constexpr (TR != 0) {
+            // Row P of the wavefront's LDS slice holds pixel P's TR channels as QPR 16-byte quads.
+            // Quad j sits in column j ^ swz(P), which makes both the row-wise writes and the
+            // transposed reads free of bank conflicts (a 64-byte row covers half the banks, so
+            // two neighbouring rows share one swizzle; a 128-byte row covers all of them).
+            constexpr int QPR = TR / 4;            // quads per row
+            constexpr int LPP = QPR;               // lanes per pixel in the transposed store
+            constexpr int PPI = 64 / LPP;          // pixels per store instruction
+            auto swz = [](int P) { return (TR == 16) ? ((P >> 1) & 3) : (P & 7); };
+            int32_t* slice = tile_lds + wave * (64 * TR);
+            {
+                const int sw = swz(lane);
+#pragma unroll
+                for (int j = 0; j < QPR; ++j) {
+                    int4 o;
+                    o.x = finish_output(acc[4 * j + 0], K);
+                    o.y = finish_output(acc[4 * j + 1], K);
+                    o.z = finish_output(acc[4 * j + 2], K);
+                    o.w = finish_output(acc[4 * j + 3], K);
+                    *reinterpret_cast<int4*>(slice + lane * TR + 4 * (j ^ sw)) = o;
+                }
+            }
+            // LDS instructions of one wavefront execute in order; this only stops the compiler
+            // from moving the reads above the writes.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int j = lane % LPP;
+            // uniform base + per-lane 32-bit byte offset; LPP neighbouring lanes write the
+            // 4*TR contiguous bytes of one pixel
+            char* dst = reinterpret_cast<char*>(y + static_cast<size_t>(tile) * 64 * Cout + cgi * G::CG);
+            if (tile * 64 + 64 <= total_pix) {  // whole tile inside the tensor (uniform)
+                int4 o[LPP];
+#pragma unroll
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    o[k] = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
+                }
+#pragma unroll
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    store_out4<true>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o[k]);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < LPP; ++k) {
+                    const int P = PPI * k + lane / LPP;
+                    const int4 o = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
+                    if (tile * 64 + P < total_pix)
+                        store_out4<true>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            if (pvalid) {
+                int32_t* dst = y + ybase + static_cast<uint32_t>(cgi * G::CG);
+#pragma unroll
+                for (int q = 0; q < G::CG; q += 4) {
+                    int4 o;
+                    o.x = finish_output(acc[q + 0], K);
+                    o.y = finish_output(acc[q + 1], K);
+                    o.z = finish_output(acc[q + 2], K);
+                    o.w = finish_output(acc[q + 3], K);
+                    store_out4<false>(dst + q, o);
+                }
+            }
+        }
+
+        if (ntile != tile)
+            load_window(ntile);
+        tile = ntile;
+        cgi = ncgi;
+    }
+}
+
+template <int CW, int S, int TR>
+hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
+                            hipStream_t stream, const int32_t* thr = nullptr,
+                            const uint2* flip = nullptr)
+{
+    using G = AregGeom<CW, TR>;
+    static_assert(G::UNITS % 2 == 0 && G::KD % kDC == 0, "pipeline geometry");
+    auto kernel = bconv3x3_areg_kernel<CW, S, TR>;
+    static const int blocks_per_cu = resident_blocks_per_cu(kernel);
+    const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
+    const int64_t tiles = (total_pix + 63) / 64;
+    const int groups_per_tile = s.Cout / G::CG;
+    const int64_t n_groups64 = tiles * groups_per_tile;
+    if (n_groups64 > 0x3fffffff)
+        return hipErrorNotSupported;
+    const int n_groups = static_cast<int>(n_groups64);
+    // Exactly the resident wavefront slots; every wavefront gets the same number of groups
+    // (+-1), so the launch is one balanced round.
+    int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
+    if (ranges > n_groups)
+        ranges = n_groups;
+    const int n_ranges = static_cast<int>(ranges);
+    const int base_groups = n_groups / n_ranges;
+    const int rem_groups = n_groups % n_ranges;
+    const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
+                       s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
+                       rem_groups, thr, flip);
+    return hipGetLastError();
+}
+
+template <int CW, int S>
+hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
+                         hipStream_t stream)
+{
+    // Transposing 32 channels writes whole 128-byte lines (HBM write traffic equals the
+    // algorithmic bytes) but costs registers and LDS; 16 channels (64-byte runs, 8-18 % extra
+    // write traffic) is the faster choice at the Bi-Real-18 shapes.  With 8 words per pixel
+    // (K = 4608) the output rate is so low that the direct store wins.
+    int tr = (CW <= 4 && s.Cout % 16 == 0) ? 16 : 0;
+    const int forced = env_int("DABNN_AREG_TR", -1);  // test hook: force the store variant
+    if (forced == 0 || (forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
+        tr = forced;
+    if (tr == 32) return launch_areg_inst<CW, S, 32>(a, w, y, s, stream);
+    if (tr == 16) return launch_areg_inst<CW, S, 16>(a, w, y, s, stream);
+    return launch_areg_inst<CW, S, 0>(a, w, y, s, stream);
+}
+
+}  // namespace
+
+// One translation unit per (word count, stride) instantiates that combination's kernels and
+// exports these two entry points; bconv_areg.hip dispatches to them.
+#define DABNN_DEFINE_AREG_ENTRY_POINTS(CW, S)                                                     \
+    hipError_t launch_areg_cw##CW##_s##S(const uint32_t* a, const uint32_t* w, int32_t* y,         \
+                                         const ConvShape& s, hipStream_t stream)                  \
+    {                                                                                             \
+        return launch_areg_s<CW, S>(a, w, y, s, stream);                                          \
+    }                                                                                             \
+    hipError_t launch_bits_cw##CW##_s##S(const uint32_t* a, const uint32_t* w, uint64_t* out,      \
+                                         const ConvShape& s, hipStream_t stream,                  \
+                                         const int32_t* thr, const uint2* flip)                   \
+    {                                                                                             \
+        return launch_areg_inst<CW, S, kBits>(a, w, reinterpret_cast<int32_t*>(out), s, stream,   \
+                                              thr, flip);                                         \
+    }
+
+}  // namespace dabnn

@@ -46,12 +46,22 @@ int make_shape(dabnn::ConvShape& s, int N, int H, int W, int Cin, int Cout, int 
     return DABNN_OK;
 }
 
+// A 1x1, stride-1, unpadded convolution is the BGEMM of the [N*H*W][Cw] activation matrix with the
+// [Cout][Cw] filter matrix.
+bool conv_is_gemm(const dabnn::ConvShape& s)
+{
+    return s.kh == 1 && s.kw == 1 && s.stride == 1 && s.pad == 0;
+}
+
 int pick_algo(const dabnn::ConvShape& s, const void* y)
 {
     // Measured on MI355X at the Bi-Real-18 shapes, the activation-stationary family is the
     // faster one wherever it applies; the filter-stationary family covers Cout % 4 != 0.
     if (dabnn::bconv_areg_supports(s, y))
         return DABNN_ALGO_AREG;
+    if (conv_is_gemm(s) &&
+        dabnn::bgemm_rowreg_supports(static_cast<int64_t>(s.N) * s.H * s.W, s.Cout, s.Cw, y))
+        return DABNN_ALGO_BGEMM;
     if (dabnn::bconv_wreg_supports(s))
         return DABNN_ALGO_WREG;
     return DABNN_ALGO_REFERENCE;
@@ -129,6 +139,11 @@ int dabnn_bconv2d_algo(const uint64_t* a, const uint64_t* w, int32_t* y, int N, 
         case DABNN_ALGO_REFERENCE: e = dabnn::launch_bconv_reference(a, w, y, s, st); break;
         case DABNN_ALGO_WREG: e = dabnn::launch_bconv_wreg(a, w, y, s, st); break;
         case DABNN_ALGO_AREG: e = dabnn::launch_bconv_areg(a, w, y, s, st); break;
+        case DABNN_ALGO_BGEMM:
+            e = conv_is_gemm(s) ? dabnn::launch_bgemm_rowreg(a, w, y, static_cast<int64_t>(s.N) * s.H * s.W,
+                                                             s.Cout, s.Cw, s.K, DABNN_BGEMM_SIGNED, st)
+                                : hipErrorNotSupported;
+            break;
         default: return DABNN_ERR_UNSUPPORTED;
     }
     if (e == hipErrorNotSupported)
@@ -141,6 +156,43 @@ int dabnn_bconv2d(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H
 {
     return dabnn_bconv2d_algo(a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad, DABNN_ALGO_AUTO,
                               stream);
+}
+
+int dabnn_bgemm(const uint64_t* A, const uint64_t* B, int32_t* C, int64_t M, int N, int Kw, int K,
+                int mode, void* stream)
+{
+    if (!A || !B || !C)
+        return DABNN_ERR_NULL;
+    if (M <= 0 || N <= 0 || Kw <= 0 || K <= 0 || K > 64LL * Kw || K >= (1 << 23))
+        return DABNN_ERR_SHAPE;
+    if (M * Kw > kMaxElems || static_cast<int64_t>(N) * Kw > kMaxElems || M * N > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    if (!aligned(A, 8) || !aligned(B, 8) || !aligned(C, 4))
+        return DABNN_ERR_ALIGN;
+    if (mode != DABNN_BGEMM_SIGNED && mode != DABNN_BGEMM_MATCHES)
+        return DABNN_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = dabnn::bgemm_rowreg_supports(M, N, Kw, C)
+                             ? dabnn::launch_bgemm_rowreg(A, B, C, M, N, Kw, K, mode, st)
+                             : dabnn::launch_bgemm_reference(A, B, C, M, N, Kw, K, mode, st);
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_im2col(const uint64_t* a, uint64_t* cols, int N, int H, int W, int Cin, int kh, int kw,
+                 int stride, int pad, void* stream)
+{
+    if (!a || !cols)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, 1, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (static_cast<int64_t>(N) * s.Ho * s.Wo * kh * kw * s.Cw > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    if (!aligned(a, 8) || !aligned(cols, 8))
+        return DABNN_ERR_ALIGN;
+    const hipError_t e = dabnn::launch_im2col(a, cols, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
 int dabnn_bconv2d_zeropad(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H, int W,

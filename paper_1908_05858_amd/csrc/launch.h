@@ -35,6 +35,15 @@ hipError_t launch_bconv_bnsign_reference(const uint64_t* a, const uint64_t* w, c
 // only).  Any shape.
 hipError_t launch_bconv_zeropad_fix(const uint64_t* w, int32_t* y, const ConvShape& s,
                                     hipStream_t stream);
+// BGEMM (Sec. 2.1.2, Eq. 1) on packed row-major A [M][Kw], B [N][Kw] -> C [M][N]; mode 0: +-1 dot
+// product K - 2*popcount(xor), mode 1: match count K - popcount(xor).
+hipError_t launch_bgemm_rowreg(const uint64_t* A, const uint64_t* B, int32_t* C, int64_t M, int N,
+                               int Kw, int K, int mode, hipStream_t stream);
+hipError_t launch_bgemm_reference(const uint64_t* A, const uint64_t* B, int32_t* C, int64_t M, int N,
+                                  int Kw, int K, int mode, hipStream_t stream);
+bool bgemm_rowreg_supports(int64_t M, int N, int Kw, const void* C);
+// Patch matrix [N*Ho*Wo][kh*kw][Cw] of a packed NHWC tensor (outside taps = zero words).
+hipError_t launch_im2col(const uint64_t* a, uint64_t* cols, const ConvShape& s, hipStream_t stream);
 bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);

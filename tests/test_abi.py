@@ -140,3 +140,18 @@ def test_zeropad_bad_arguments(lib):
     assert lib.dabnn_bconv2d_zeropad(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2   # pad >= k
     assert lib.dabnn_bconv2d_zeropad(a, w, y, 1, 4, 4, 64, 64, 3, 3, 0, 1, None) == 2   # stride 0
     assert lib.dabnn_bconv2d_zeropad(a, w, P(0x30002), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
+
+
+def test_bgemm_and_im2col_bad_arguments(lib):
+    P = ctypes.c_void_p
+    A, B, C = P(0x10000), P(0x20000), P(0x30000)
+    assert lib.dabnn_bgemm(A, B, P(0), 4, 4, 1, 64, 0, None) == 1
+    assert lib.dabnn_bgemm(A, B, C, 0, 4, 1, 64, 0, None) == 2
+    assert lib.dabnn_bgemm(A, B, C, 4, 4, 1, 65, 0, None) == 2       # K exceeds the row's bits
+    assert lib.dabnn_bgemm(A, B, C, 4, 4, 1, 0, 0, None) == 2
+    assert lib.dabnn_bgemm(A, B, C, 1 << 20, 1 << 12, 1, 64, 0, None) == 2  # C too large
+    assert lib.dabnn_bgemm(P(0x10004), B, C, 4, 4, 1, 64, 0, None) == 3
+    assert lib.dabnn_bgemm(A, B, C, 4, 4, 1, 64, 2, None) == 4       # unknown mode
+    assert lib.dabnn_im2col(A, P(0), 1, 4, 4, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_im2col(A, B, 1, 4, 4, 64, 3, 3, 1, 3, None) == 2
+    assert lib.dabnn_im2col(A, P(0x20001), 1, 4, 4, 64, 3, 3, 1, 1, None) == 3

@@ -229,6 +229,72 @@ def test_bconv2d_zeropad_full_batch_layer(dabnn, oracle):
     assert np.array_equal(d, np.broadcast_to(d[:1], d.shape))
 
 
+# ------------------------------------------------------------------------------ BGEMM (Eq. 1)
+
+BGEMM_SHAPES = [  # M, N, K  (Kw = ceil(K/64)); fast kernel: N % 16 == 0 and 2*Kw in its list
+    (200, 64, 64), (1000, 32, 128), (130, 16, 190), (64, 48, 256), (65, 16, 384), (300, 128, 512),
+    (77, 16, 576), (100, 32, 768), (50, 16, 1024), (90, 16, 1152), (40, 16, 1536), (33, 16, 2048),
+    (70, 32, 2304), (20, 16, 3072), (10, 16, 4096), (129, 16, 4608), (4100, 256, 64),
+    # reference kernel: other row lengths, N not a multiple of 16, tiny shapes
+    (10, 10, 64), (33, 16, 320), (7, 16, 5000), (1, 1, 1), (64, 17, 128),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", BGEMM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bgemm(dabnn, oracle, shape, mode):
+    M, N, K = shape
+    print("bgemm", shape, mode, flush=True)
+    xa = wl.activations((M, K), 881 + M + N)
+    xb = wl.weights((N, K), 882 + K, p_plus=0.4)
+    A = dabnn.bitpack(gpu(xa))   # rows are "pixels" of K channels: tails come out as 0
+    B = dabnn.bitpack(gpu(xb))
+    C = dabnn.bgemm(A, B, K, mode)
+    want = oracle.bgemm_signed(oracle.sign(xa), oracle.sign(xb), mode)
+    assert C.dtype == torch.int32 and tuple(C.shape) == (M, N)
+    assert np.array_equal(C.cpu().numpy(), want)
+
+
+IM2COL_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 32, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
+    (2, 7, 7, 512, 64, 3, 1, 1), (1, 10, 17, 200, 33, 3, 2, 1), (1, 12, 12, 64, 16, 5, 1, 2),
+    (2, 6, 6, 100, 48, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("shape", IM2COL_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_im2col_and_conv_as_bgemm(dabnn, oracle, shape):
+    """The patch matrix word for word, and the BGEMM route (Fig. 4's comparison method) against the
+    convolution oracle and against the direct kernel."""
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("im2col", shape, flush=True)
+    x = wl.activations((N, H, W, Cin), 991 + sum(shape))
+    wf = wl.weights((Cout, k, k, Cin), 992 + sum(shape), p_plus=0.3)
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    cols = dabnn.im2col(a, Cin, k, k, stride, pad)
+    Cw = (Cin + 63) // 64
+    patch = oracle.im2col_signed(oracle.sign(x), k, k, stride, pad)      # [M, k*k, Cin]
+    want_cols = oracle.bitpack(patch).reshape(patch.shape[0], k * k * Cw)
+    assert np.array_equal(words(cols), want_cols)
+    y = dabnn.bgemm(cols, wp.reshape(Cout, k * k * Cw), k * k * Cin)
+    want = oracle.bconv2d(x, wf, stride, pad)
+    assert np.array_equal(y.cpu().numpy().reshape(want.shape), want)
+    assert torch.equal(y.reshape(want.shape), dabnn.bconv2d(a, wp, Cin, stride, pad))
+
+
+@pytest.mark.parametrize("shape", [(2, 14, 14, 64, 64), (3, 9, 7, 128, 32), (1, 28, 28, 256, 512),
+                                   (2, 7, 7, 512, 128), (1, 5, 5, 100, 16)],
+                         ids=lambda s: "-".join(map(str, s)))
+def test_pointwise_conv_runs_as_bgemm(dabnn, oracle, shape):
+    N, H, W, Cin, Cout = shape
+    assert dabnn.pick_algo(N, H, W, Cin, Cout, 1, 1, 1, 0) == dabnn.ALGO_BGEMM
+    run_conv(dabnn, oracle, N, H, W, Cin, Cout, 1, 1, 0, seed=555 + sum(shape), algo=dabnn.ALGO_BGEMM)
+    run_conv(dabnn, oracle, N, H, W, Cin, Cout, 1, 1, 0, seed=556 + sum(shape), algo=0)
+    # strided or padded 1x1 convolutions are not a plain matrix product
+    assert dabnn.pick_algo(N, H, W, Cin, Cout, 1, 1, 2, 0) == dabnn.ALGO_REFERENCE
+
+
 # ------------------------------------------------------------------------------- fused BN + sign
 
 def _bn_params(C, seed):
