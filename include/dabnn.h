@@ -137,6 +137,26 @@ int dabnn_im2col(const uint64_t *a, uint64_t *cols, int N, int H, int W, int Cin
                  int stride, int pad, void *stream);
 
 /*
+ * Expanded-operand comparison route (not the default path).  CDNA4 has no 1-bit matrix
+ * instruction, but +-1 is exact in int8: with every bit expanded to a byte the binary convolution
+ * of Sec. 2.1.2 becomes an int8 implicit GEMM on the matrix cores, y = sum a*w with int32
+ * accumulation, bit-identical to K - 2*popcount(a XOR w) of Eq. 6-7.  Provided so that the
+ * XOR/popcount kernels can be measured against it, the 8x operand expansion included.
+ *
+ * dabnn_expand_int8: packed rows -> int8, +1 for bit 0 and -1 for bit 1.
+ *   bits : u64 [rows][C/64]  device          out : i8 [rows][C]  device, 16-byte aligned
+ *   C % 64 == 0 (DABNN_ERR_UNSUPPORTED otherwise).  Works for activations (rows = N*H*W) and for
+ *   packed filters (rows = Cout*kh*kw) alike.
+ * dabnn_bconv2d_int8: the convolution of dabnn_bconv2d on expanded operands.
+ *   a8 : i8 [N][H][W][Cin]   w8 : i8 [Cout][kh][kw][Cin]   values +-1, device, 16-byte aligned
+ *   y  : i32 [N][Ho][Wo][Cout]  device.  Out-of-image taps count as +1.
+ *   Cin % 64 == 0 and Cout % 64 == 0 (DABNN_ERR_UNSUPPORTED otherwise); any kernel size, stride, pad.
+ */
+int dabnn_expand_int8(const uint64_t *bits, int8_t *out, int64_t rows, int C, void *stream);
+int dabnn_bconv2d_int8(const int8_t *a8, const int8_t *w8, int32_t *y, int N, int H, int W, int Cin,
+                       int Cout, int kh, int kw, int stride, int pad, void *stream);
+
+/*
  * Binary convolution with ZERO padding.  The paper builds its binary convolution on the standard
  * ONNX Sign and Convolution operators (Table 1 caption, Sec. 3), and ONNX Convolution pads with 0:
  * a tap outside the image contributes nothing, where dabnn_bconv2d counts it as +1 in every

@@ -41,6 +41,8 @@ def load():
     lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
     lib.dabnn_bgemm.argtypes, lib.dabnn_bgemm.restype = [vp] * 3 + [i64, i32, i32, i32, i32, vp], i32
     lib.dabnn_im2col.argtypes, lib.dabnn_im2col.restype = [vp] * 2 + [i32] * 8 + [vp], i32
+    lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
+    lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
@@ -53,7 +55,8 @@ def load():
 
 EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
-           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col"]
+           "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
+           "dabnn_expand_int8", "dabnn_bconv2d_int8"]
 
 
 def status_string(status):
@@ -173,6 +176,36 @@ def im2col(a, Cin, kh, kw, stride=1, pad=0, out=None):
         out = torch.empty((N * Ho * Wo, kh * kw * Cw), dtype=torch.int64, device=a.device)
     _check(load().dabnn_im2col(_dev(a, torch.int64, "a"), _dev(out, torch.int64, "out"), N, H, W, Cin,
                                kh, kw, stride, pad, _stream()), "dabnn_im2col")
+    return out
+
+
+def expand_int8(bits, C, out=None):
+    """Packed int64 [..., C/64] -> int8 [..., C], +1 for bit 0 and -1 for bit 1 (C % 64 == 0)."""
+    if bits.shape[-1] * 64 != C:
+        raise ValueError("packed word count does not match C")
+    rows = bits.numel() // bits.shape[-1]
+    if out is None:
+        out = torch.empty(tuple(bits.shape[:-1]) + (C,), dtype=torch.int8, device=bits.device)
+    _check(load().dabnn_expand_int8(_dev(bits, torch.int64, "bits"), _dev(out, torch.int8, "out"), rows, C,
+                                    _stream()), "dabnn_expand_int8")
+    return out
+
+
+def bconv2d_int8(a8, w8, stride=1, pad=0, out=None):
+    """Comparison route: a8 int8 [N,H,W,Cin], w8 int8 [Cout,kh,kw,Cin] (+-1) -> int32 [N,Ho,Wo,Cout]
+    on the int8 matrix cores."""
+    N, H, W, Cin = a8.shape
+    Cout, kh, kw, Cin2 = w8.shape
+    if Cin != Cin2:
+        raise ValueError("channel counts differ")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_int8")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, Cout), dtype=torch.int32, device=a8.device)
+    _check(load().dabnn_bconv2d_int8(_dev(a8, torch.int8, "a8"), _dev(w8, torch.int8, "w8"),
+                                     _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, kh, kw, stride,
+                                     pad, _stream()), "dabnn_bconv2d_int8")
     return out
 
 

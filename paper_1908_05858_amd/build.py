@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libdabnn.so")
-SOURCES = (["dabnn_api.hip", "bitpack.hip", "bconv.hip", "bconv_areg.hip", "bconv_zeropad.hip", "bgemm.hip"] +
+SOURCES = (["dabnn_api.hip", "bitpack.hip", "bconv.hip", "bconv_areg.hip", "bconv_zeropad.hip", "bgemm.hip", "bconv_mfma.hip"] +
            [f"bconv_areg_cw{cw}_s{st}.hip" for cw in (8, 4, 2, 1) for st in (1, 2)])
 # -packed-fp32-ops is switched off for every HIP translation unit of this project.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

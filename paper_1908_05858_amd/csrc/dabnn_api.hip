@@ -195,6 +195,42 @@ int dabnn_im2col(const uint64_t* a, uint64_t* cols, int N, int H, int W, int Cin
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
+int dabnn_expand_int8(const uint64_t* bits, int8_t* out, int64_t rows, int C, void* stream)
+{
+    if (rows < 0 || C <= 0 || rows > (1LL << 40) / C)
+        return DABNN_ERR_SHAPE;
+    if (rows == 0)
+        return DABNN_OK;
+    if (!bits || !out)
+        return DABNN_ERR_NULL;
+    if (!aligned(bits, 8) || !aligned(out, 16))
+        return DABNN_ERR_ALIGN;
+    if (C % 64 != 0)
+        return DABNN_ERR_UNSUPPORTED;
+    const hipError_t e = dabnn::launch_expand_pm1(bits, out, rows, C, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_bconv2d_int8(const int8_t* a8, const int8_t* w8, int32_t* y, int N, int H, int W, int Cin,
+                       int Cout, int kh, int kw, int stride, int pad, void* stream)
+{
+    if (!a8 || !w8 || !y)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (static_cast<int64_t>(N) * H * W * Cin > kMaxElems ||
+        static_cast<int64_t>(Cout) * kh * kw * Cin > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    if (!aligned(a8, 16) || !aligned(w8, 16) || !aligned(y, 4))
+        return DABNN_ERR_ALIGN;
+    if (!dabnn::bconv_mfma_supports(s))
+        return DABNN_ERR_UNSUPPORTED;
+    const hipError_t e = dabnn::launch_bconv_mfma_i8(a8, w8, y, s, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
 int dabnn_bconv2d_zeropad(const uint64_t* a, const uint64_t* w, int32_t* y, int N, int H, int W,
                           int Cin, int Cout, int kh, int kw, int stride, int pad, void* stream)
 {

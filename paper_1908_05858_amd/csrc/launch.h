@@ -44,6 +44,12 @@ hipError_t launch_bgemm_reference(const uint64_t* A, const uint64_t* B, int32_t*
 bool bgemm_rowreg_supports(int64_t M, int N, int Kw, const void* C);
 // Patch matrix [N*Ho*Wo][kh*kw][Cw] of a packed NHWC tensor (outside taps = zero words).
 hipError_t launch_im2col(const uint64_t* a, uint64_t* cols, const ConvShape& s, hipStream_t stream);
+// Expanded-operand comparison route: bits -> +-1 int8, and an int8 matrix-core implicit GEMM.
+hipError_t launch_expand_pm1(const uint64_t* bits, int8_t* out, int64_t rows, int C,
+                             hipStream_t stream);
+hipError_t launch_bconv_mfma_i8(const int8_t* a8, const int8_t* w8, int32_t* y, const ConvShape& s,
+                                hipStream_t stream);
+bool bconv_mfma_supports(const ConvShape& s);
 bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);

@@ -155,3 +155,18 @@ def test_bgemm_and_im2col_bad_arguments(lib):
     assert lib.dabnn_im2col(A, P(0), 1, 4, 4, 64, 3, 3, 1, 1, None) == 1
     assert lib.dabnn_im2col(A, B, 1, 4, 4, 64, 3, 3, 1, 3, None) == 2
     assert lib.dabnn_im2col(A, P(0x20001), 1, 4, 4, 64, 3, 3, 1, 1, None) == 3
+
+
+def test_int8_route_bad_arguments(lib):
+    P = ctypes.c_void_p
+    a, w, y = P(0x10000), P(0x20000), P(0x30000)
+    assert lib.dabnn_expand_int8(a, P(0), 4, 64, None) == 1
+    assert lib.dabnn_expand_int8(a, w, -1, 64, None) == 2
+    assert lib.dabnn_expand_int8(a, P(0x20008), 4, 64, None) == 3
+    assert lib.dabnn_expand_int8(a, w, 4, 80, None) == 4
+    assert lib.dabnn_expand_int8(P(0), P(0), 0, 64, None) == 0
+    assert lib.dabnn_bconv2d_int8(a, w, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2
+    assert lib.dabnn_bconv2d_int8(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
+    assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 80, 64, 3, 3, 1, 1, None) == 4
+    assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 64, 48, 3, 3, 1, 1, None) == 4

@@ -295,6 +295,47 @@ def test_pointwise_conv_runs_as_bgemm(dabnn, oracle, shape):
     assert dabnn.pick_algo(N, H, W, Cin, Cout, 1, 1, 2, 0) == dabnn.ALGO_REFERENCE
 
 
+# ------------------------------------------------- expanded-operand (int8 matrix core) comparison
+
+INT8_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (1, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 192, 3, 1, 1),
+    (2, 7, 7, 512, 512, 3, 1, 1), (5, 11, 6, 64, 256, 3, 1, 1), (1, 12, 12, 64, 64, 5, 1, 2),
+    (2, 6, 6, 128, 64, 1, 1, 0), (4, 56, 56, 64, 64, 3, 1, 1), (1, 7, 9, 192, 128, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("shape", INT8_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_int8_matrix_core_route(dabnn, oracle, shape):
+    """Bits -> +-1 bytes (against the sign oracle), then the int8 implicit GEMM against the
+    convolution oracle and the XOR/popcount kernel."""
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("int8", shape, flush=True)
+    x = wl.activations((N, H, W, Cin), 661 + sum(shape))
+    wf = wl.weights((Cout, k, k, Cin), 662 + sum(shape), p_plus=0.3)
+    a = dabnn.bitpack(gpu(x))
+    wp = dabnn.pack_weights(gpu(wf))
+    a8 = dabnn.expand_int8(a, Cin)
+    w8 = dabnn.expand_int8(wp, Cin)
+    assert np.array_equal(a8.cpu().numpy(), oracle.sign(x).astype(np.int8))
+    assert np.array_equal(w8.cpu().numpy(), oracle.sign(wf).astype(np.int8))
+    n_out = N * oracle.conv_out_dim(H, k, stride, pad) * oracle.conv_out_dim(W, k, stride, pad) * Cout
+    buf = torch.full((n_out + 512,), -123456789, dtype=torch.int32, device="cuda")
+    want = oracle.bconv2d(x, wf, stride, pad)
+    out = buf[256:256 + n_out].view(want.shape)
+    dabnn.bconv2d_int8(a8, w8, stride, pad, out=out)
+    assert torch.all(buf[:256] == -123456789) and torch.all(buf[-256:] == -123456789)
+    assert np.array_equal(out.cpu().numpy(), want)
+    assert torch.equal(out, dabnn.bconv2d(a, wp, Cin, stride, pad))
+
+
+def test_int8_route_refuses_other_channel_counts(dabnn):
+    a8 = torch.ones((1, 4, 4, 80), dtype=torch.int8, device="cuda")
+    w8 = torch.ones((64, 3, 3, 80), dtype=torch.int8, device="cuda")
+    with pytest.raises(dabnn.DabnnError) as e:
+        dabnn.bconv2d_int8(a8, w8, 1, 1)
+    assert e.value.status == 4
+
+
 # ------------------------------------------------------------------------------- fused BN + sign
 
 def _bn_params(C, seed):
