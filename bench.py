@@ -153,6 +153,34 @@ def main():
         torch.cuda.synchronize()
         fused_ms = (time.perf_counter() - t3) * 1e3 / args.steps
 
+    # Comparison row: the same convolutions on the int8 matrix cores with every bit expanded to a
+    # +-1 byte (dabnn_expand_int8 + dabnn_bconv2d_int8).  One step = 16 x (expand the packed
+    # activations, convolve); filters are expanded ahead of time like they are packed ahead of time.
+    mfma_ms = mfma_conv_ms = None
+    if all(L.Cin % 64 == 0 and L.Cout % 64 == 0 for L in layers):
+        w8s = [binding.expand_int8(wps[li], L.Cin) for li, L in enumerate(layers)]
+        a8s = [torch.empty((N, L.H, L.W, L.Cin), dtype=torch.int8, device="cuda") for L in layers]
+
+        def mfma_step(expand=True):
+            for li, L in enumerate(layers):
+                if expand:
+                    binding.expand_int8(acts[li], L.Cin, out=a8s[li])
+                binding.bconv2d_int8(a8s[li], w8s[li], L.stride, 1, out=ys[li])
+        mfma_step()
+        torch.cuda.synchronize()
+        k_cmp = max(4, args.steps // 4)
+        t4 = time.perf_counter()
+        for k in range(k_cmp):
+            mfma_step()
+        torch.cuda.synchronize()
+        mfma_ms = (time.perf_counter() - t4) * 1e3 / k_cmp
+        t5 = time.perf_counter()
+        for k in range(k_cmp):
+            mfma_step(expand=False)
+        torch.cuda.synchronize()
+        mfma_conv_ms = (time.perf_counter() - t5) * 1e3 / k_cmp
+        del w8s, a8s
+
     ops = [L.ops(N) for L in layers]
     total_ops = float(sum(ops))
     pack_bytes = [xs[li].numel() * 4 + acts[li].numel() * 8 for li in range(len(layers))]
@@ -217,6 +245,16 @@ def main():
         },
         "per_layer": per_layer,
     }
+    if mfma_ms is not None:
+        result["int8_mfma_comparison"] = {
+            "what": "16 x (dabnn_expand_int8 of the packed activations + dabnn_bconv2d_int8 on "
+                    "v_mfma_i32_32x32x32_i8), same outputs; comparison only, not the method's path",
+            "ms_per_step": round(mfma_ms, 4),
+            "GOPS": round(total_ops / (mfma_ms * 1e-3) / 1e9, 1),
+            "conv_only_ms_per_step": round(mfma_conv_ms, 4),
+            "conv_only_GOPS": round(total_ops / (mfma_conv_ms * 1e-3) / 1e9, 1),
+            "conv_only_frac_of_int8_mfma_peak": round(total_ops / (mfma_conv_ms * 1e-3) / 5.0e15, 4),
+        }
     if fused_ms is not None:
         result["fused_bnsign"] = {
             "what": "16 x dabnn_bconv2d_bnsign (conv + BN threshold + bit-pack of the result in one "
