@@ -123,6 +123,7 @@ __device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
 //   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
 //   an output word).
 constexpr int kBits = -1;
+constexpr int kTailTR = 16;  // the store mode whose uneven remainder is split into small pieces
 constexpr int kDC = 6;
 template <int CW, int TR>
 struct AregGeom {
@@ -169,10 +170,9 @@ template <int CW, int S, int TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
-    int n_ranges, int base_groups, int rem_groups, const int32_t* __restrict__ thr,
-    const uint2* __restrict__ flip)
+    int n_ranges, int base_groups, int rem_groups, int tail_first, int tail_base, int tail_rem,
+    const int32_t* __restrict__ thr, const uint2* __restrict__ flip)
 {
-    using G = AregGeom<CW, TR>;
     // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
     __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : 4];
 
@@ -181,16 +181,8 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     const int gw = blockIdx.x * 4 + wave;
     if (gw >= n_ranges)
         return;  // the grid is rounded up to whole workgroups
-    // balanced contiguous partition of (tile, channel group) pairs, channel group fastest
-    int g = gw * base_groups + (gw < rem_groups ? gw : rem_groups);
-    const int g_begin = g;
-    const int g_end = g + base_groups + (gw < rem_groups ? 1 : 0);
-    if (g >= g_end)
-        return;
-    int tile = g / groups_per_tile;
-    int cgi = g - tile * groups_per_tile;
 
-    uint32_t areg[G::KD];
+    uint32_t areg[18 * CW];
     bool pvalid = false;
     uint32_t ybase = 0;
     // The 3x3xCw window under this lane's output pixel; taps outside the image become zero
@@ -218,29 +210,39 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                 const bool v = rv && static_cast<unsigned>(wi0 + j) < static_cast<unsigned>(W);
                 const uint32_t keep = v ? 0xffffffffu : 0u;
                 const uint32_t off =
-                    v ? static_cast<uint32_t>(top_left + i * W + j) * (G::D * 4u) : 0u;
+                    v ? static_cast<uint32_t>(top_left + i * W + j) * ((2 * CW) * 4u) : 0u;
                 const char* src = base + off;
-                if constexpr (G::D == 2) {
+                if constexpr ((2 * CW) == 2) {
                     const uint2 u = *reinterpret_cast<const uint2*>(src);
                     areg[(i * 3 + j) * 2 + 0] = u.x & keep;
                     areg[(i * 3 + j) * 2 + 1] = u.y & keep;
                 } else {
 #pragma unroll
-                    for (int d = 0; d < G::D; d += 4) {
+                    for (int d = 0; d < (2 * CW); d += 4) {
                         const uint4 u = *reinterpret_cast<const uint4*>(src + d * 4);
-                        areg[(i * 3 + j) * G::D + d + 0] = u.x & keep;
-                        areg[(i * 3 + j) * G::D + d + 1] = u.y & keep;
-                        areg[(i * 3 + j) * G::D + d + 2] = u.z & keep;
-                        areg[(i * 3 + j) * G::D + d + 3] = u.w & keep;
+                        areg[(i * 3 + j) * (2 * CW) + d + 0] = u.x & keep;
+                        areg[(i * 3 + j) * (2 * CW) + d + 1] = u.y & keep;
+                        areg[(i * 3 + j) * (2 * CW) + d + 2] = u.z & keep;
+                        areg[(i * 3 + j) * (2 * CW) + d + 3] = u.w & keep;
                     }
                 }
             }
         }
     };
+    // Processes the (tile, channel group) pairs [g, g_end), channel group fastest, in store mode
+    // TRX (its group size decides what a "group" is).
+    auto run_range = [&](auto mode, int g, const int g_end, const int groups_per_tile) {
+    constexpr int TRX = decltype(mode)::value;
+    using G = AregGeom<CW, TRX>;
+    if (g >= g_end)
+        return;
+    const int g_begin = g;
+    int tile = g / groups_per_tile;
+    int cgi = g - tile * groups_per_tile;
     load_window(tile);
 
     uint32_t sb0[G::SB], sb1[G::SB];
-    areg_load_unit<CW, TR, 0>(sb0, w, cgi * G::CG);
+    areg_load_unit<CW, TRX, 0>(sb0, w, cgi * G::CG);
     uint32_t bits32 = 0;  // fused bit-pack output under construction
 
     for (; g < g_end; ++g) {
@@ -254,8 +256,8 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         // The group's 16 thresholds, fetched with vector loads at the start of the group (every
         // lane reads the same 64 bytes) so that they neither occupy SGPRs nor disturb the
         // scalar-load pipeline; they are first used after the last unit.
-        int thr_v[TR == kBits ? 16 : 1];
-        if constexpr (TR == kBits) {
+        int thr_v[TRX == kBits ? 16 : 1];
+        if constexpr (TRX == kBits) {
             uint32_t lane_off = 0;
             asm volatile("" : "+v"(lane_off));  // keeps the address per-lane: a vector load
             const int4* tp = reinterpret_cast<const int4*>(thr + cgi * 16 + lane_off);
@@ -276,22 +278,22 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             schedule_fence();
             if constexpr (u + 1 < G::UNITS) {
                 if constexpr (u % 2 == 0)
-                    areg_load_unit<CW, TR, u + 1>(sb1, w, cgi * G::CG);
+                    areg_load_unit<CW, TRX, u + 1>(sb1, w, cgi * G::CG);
                 else
-                    areg_load_unit<CW, TR, u + 1>(sb0, w, cgi * G::CG);
+                    areg_load_unit<CW, TRX, u + 1>(sb0, w, cgi * G::CG);
             } else {
                 if (g + 1 < g_end)  // first unit of the next group (UNITS is even: buffer 0)
-                    areg_load_unit<CW, TR, 0>(sb0, w, ncgi * G::CG);
+                    areg_load_unit<CW, TRX, 0>(sb0, w, ncgi * G::CG);
             }
             schedule_fence();
             if constexpr (u % 2 == 0)
-                areg_compute_unit<CW, TR, u>(sb0, acc, areg);
+                areg_compute_unit<CW, TRX, u>(sb0, acc, areg);
             else
-                areg_compute_unit<CW, TR, u>(sb1, acc, areg);
+                areg_compute_unit<CW, TRX, u>(sb1, acc, areg);
             schedule_fence();
         });
 
-        if constexpr (TR == kBits) {
+        if constexpr (TRX == kBits) {
             // Fused threshold + bit-pack: y < thr  <=>  (K - thr) - 2d < 0.  The 16 channels are
             // shifted in in ascending order and bit-reversed into place afterwards.  An even
             // group whose odd partner belongs to this wavefront too is held back, and the pair
@@ -317,16 +319,16 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     reinterpret_cast<uint16_t*>(y)[2 * half_index + (odd ? 1 : 0)] =
                         static_cast<uint16_t>((rev >> 16) ^ fl16);
             }
-        } else if constexpr (TR != 0) {
-            // Row P of the wavefront's LDS slice holds pixel P's TR channels as QPR 16-byte quads.
+        } else if constexpr (TRX != 0) {
+            // Row P of the wavefront's LDS slice holds pixel P's TRX channels as QPR 16-byte quads.
             // Quad j sits in column j ^ swz(P), which makes both the row-wise writes and the
             // transposed reads free of bank conflicts (a 64-byte row covers half the banks, so
             // two neighbouring rows share one swizzle; a 128-byte row covers all of them).
-            constexpr int QPR = TR / 4;            // quads per row
+            constexpr int QPR = TRX / 4;            // quads per row
             constexpr int LPP = QPR;               // lanes per pixel in the transposed store
             constexpr int PPI = 64 / LPP;          // pixels per store instruction
-            auto swz = [](int P) { return (TR == 16) ? ((P >> 1) & 3) : (P & 7); };
-            int32_t* slice = tile_lds + wave * (64 * TR);
+            auto swz = [](int P) { return (TRX == 16) ? ((P >> 1) & 3) : (P & 7); };
+            int32_t* slice = tile_lds + wave * (64 * TRX);
             {
                 const int sw = swz(lane);
 #pragma unroll
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     o.y = finish_output(acc[4 * j + 1], K);
                     o.z = finish_output(acc[4 * j + 2], K);
                     o.w = finish_output(acc[4 * j + 3], K);
-                    *reinterpret_cast<int4*>(slice + lane * TR + 4 * (j ^ sw)) = o;
+                    *reinterpret_cast<int4*>(slice + lane * TRX + 4 * (j ^ sw)) = o;
                 }
             }
             // LDS instructions of one wavefront execute in order; this only stops the compiler
@@ -346,14 +348,14 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const int j = lane % LPP;
             // uniform base + per-lane 32-bit byte offset; LPP neighbouring lanes write the
-            // 4*TR contiguous bytes of one pixel
+            // 4*TRX contiguous bytes of one pixel
             char* dst = reinterpret_cast<char*>(y + static_cast<size_t>(tile) * 64 * Cout + cgi * G::CG);
             if (tile * 64 + 64 <= total_pix) {  // whole tile inside the tensor (uniform)
                 int4 o[LPP];
 #pragma unroll
                 for (int k = 0; k < LPP; ++k) {
                     const int P = PPI * k + lane / LPP;
-                    o[k] = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
+                    o[k] = *reinterpret_cast<const int4*>(slice + P * TRX + 4 * (j ^ swz(P)));
                 }
 #pragma unroll
                 for (int k = 0; k < LPP; ++k) {
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 #pragma unroll
                 for (int k = 0; k < LPP; ++k) {
                     const int P = PPI * k + lane / LPP;
-                    const int4 o = *reinterpret_cast<const int4*>(slice + P * TR + 4 * (j ^ swz(P)));
+                    const int4 o = *reinterpret_cast<const int4*>(slice + P * TRX + 4 * (j ^ swz(P)));
                     if (tile * 64 + P < total_pix)
                         store_out4<true>(dst + (static_cast<uint32_t>(P) * Cout + 4 * j) * 4u, o);
                 }
@@ -391,6 +393,21 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
         tile = ntile;
         cgi = ncgi;
     }
+    };
+
+    // Every wavefront first takes the same number (+-1) of whole groups, a contiguous range.
+    const int g0 = gw * base_groups + (gw < rem_groups ? gw : rem_groups);
+    run_range(std::integral_constant<int, TR>{}, g0, g0 + base_groups + (gw < rem_groups ? 1 : 0),
+              groups_per_tile);
+    // The groups that do not divide evenly over the wavefronts are handed out in pieces of 4 (or
+    // 8) channels through the direct-store path, so that no wavefront -- and no SIMD -- carries a
+    // whole extra group.
+    if constexpr (TR == kTailTR) {
+        using GT = AregGeom<CW, 0>;
+        const int t0 = tail_first + gw * tail_base + (gw < tail_rem ? gw : tail_rem);
+        run_range(std::integral_constant<int, 0>{}, t0, t0 + tail_base + (gw < tail_rem ? 1 : 0),
+                  Cout / GT::CG);
+    }
 }
 
 template <int CW, int S, int TR>
@@ -412,15 +429,34 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     // Exactly the resident wavefront slots; every wavefront gets the same number of groups
     // (+-1), so the launch is one balanced round.
     int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
+    const int forced_slots = env_int("DABNN_AREG_SLOTS", 0);  // test hook: pretend a smaller chip
+    if (forced_slots > 0)
+        ranges = forced_slots;
     if (ranges > n_groups)
         ranges = n_groups;
     const int n_ranges = static_cast<int>(ranges);
     const int base_groups = n_groups / n_ranges;
-    const int rem_groups = n_groups % n_ranges;
+    int rem_groups = n_groups % n_ranges;
+    // A small remainder (few wavefronts with a whole group more, i.e. a few SIMDs that finish a
+    // group late) is instead split into direct-store pieces of 4 (8) channels and spread over
+    // all wavefronts.  Measured at batch 256: -3 % kernel time at 14x14x256->256 (remainder
+    // 6 % of the wavefronts); a large remainder is cheaper as whole groups, because the pieces
+    // use the slower direct store and each needs its own window.
+    int tail_first = 0, tail_base = 0, tail_rem = 0;
+    const int tail_mode = env_int("DABNN_AREG_TAIL", 1);  // test hook: 0 never, 2 always
+    if (TR == kTailTR && rem_groups > 0 &&
+        (tail_mode == 2 || (tail_mode == 1 && rem_groups * 4 <= n_ranges))) {
+        constexpr int pieces = G::CG / AregGeom<CW, 0>::CG;
+        const int n_tail = rem_groups * pieces;
+        tail_first = base_groups * n_ranges * pieces;
+        tail_base = n_tail / n_ranges;
+        tail_rem = n_tail % n_ranges;
+        rem_groups = 0;
+    }
     const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
                        s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
-                       rem_groups, thr, flip);
+                       rem_groups, tail_first, tail_base, tail_rem, thr, flip);
     return hipGetLastError();
 }
 

@@ -183,6 +183,27 @@ def test_kernel_variants(dabnn, oracle, env, monkeypatch):
         run_conv(dabnn, oracle, *shape, seed=31337 + sum(shape), algo=algo)
 
 
+@pytest.mark.parametrize("slots", [1, 3, 7, 40, 1000])
+@pytest.mark.parametrize("tail", ["0", "2"])
+def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, monkeypatch):
+    """The split of (tile, channel group) pairs over wavefronts, with the wavefront count forced
+    small so that ranges span several tiles, and the uneven remainder handed out either as whole
+    groups or as direct-store pieces."""
+    monkeypatch.setenv("DABNN_AREG_SLOTS", str(slots))
+    monkeypatch.setenv("DABNN_AREG_TAIL", tail)
+    for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
+                  (1, 23, 17, 64, 48, 3, 1, 1), (2, 7, 7, 512, 64, 3, 1, 1)]:
+        print("split", slots, tail, shape, flush=True)
+        run_conv(dabnn, oracle, *shape, seed=1717 + slots + sum(shape), algo=3)
+    shape = (2, 14, 14, 128, 128, 3, 1, 1)
+    x = wl.activations(shape[:4], 1718 + slots)
+    wf = wl.weights((128, 3, 3, 128), 1719 + slots)
+    gamma, beta, mean, var = _bn_params(128, 1720 + slots)
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * 128)
+    got = dabnn.bconv2d_bnsign(dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf)), thr, flip, 128, 1, 1)
+    assert np.array_equal(words(got), oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, 1, 1))
+
+
 # ------------------------------------------------------------------- zero padding (ONNX Convolution)
 
 ZEROPAD_SHAPES = ODD_SHAPES + [
