@@ -5,7 +5,8 @@ A thin ctypes loader around ``dabnn_oracle.c`` (plain C + OpenMP).  Only ``tests
 package.  It imports nothing from the GPU package and the GPU package imports nothing from here.
 
 What each function computes, with the passage it follows, is stated in ``dabnn_oracle.c``:
-``sign`` / ``bitpack`` follow Sec. 2.1.1; ``bconv2d`` is the +-1 float cross-correlation that
+``sign`` / ``bitpack`` / ``bitpack_i32`` follow Sec. 2.1.1; ``nhwc_to_nc1hwc2`` is the layout of
+Sec. 2.1.2; ``bconv2d`` is the +-1 float cross-correlation that
 Eq. 1 and Eq. 6-7 (Sec. 2.1.2) must equal (``bconv2d_zeropad``: the same with the zero padding
 of the ONNX Convolution operator the paper builds on); ``bgemm_signed`` is Eq. 1 and the dot
 product it stands for, ``im2col_signed`` the patch matrix that turns a convolution into that
@@ -52,13 +53,16 @@ def _load():
     lib.oracle_conv_out_dim.argtypes = [i32] * 4
     lib.oracle_bconv2d.argtypes = [vp, vp, vp] + [i32] * 9
     lib.oracle_bconv2d_zeropad.argtypes = [vp, vp, vp] + [i32] * 9
+    lib.oracle_bitpack_i32.argtypes = [vp, vp, i64, i32]
+    lib.oracle_nhwc_to_nc1hwc2.argtypes = [vp, vp] + [i32] * 4
     lib.oracle_bgemm.argtypes = [vp, vp, vp, i64, i32, i32, i32]
     lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
     lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
     lib.oracle_bconv2d_bnsign.argtypes = [vp] * 6 + [ctypes.c_float, vp] + [i32] * 9
     for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
               lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign,
-              lib.oracle_bconv2d_zeropad, lib.oracle_bgemm):
+              lib.oracle_bconv2d_zeropad, lib.oracle_bgemm, lib.oracle_bitpack_i32,
+              lib.oracle_nhwc_to_nc1hwc2):
         f.restype = i32
     _lib = lib
     return lib
@@ -89,6 +93,24 @@ def bitpack(x, sign_rule=SIGN_BIT):
     n_pixels = x.size // C if C else 0
     out = np.empty(x.shape[:-1] + (words,), dtype=np.uint64)
     _check(_load().oracle_bitpack(x.ctypes.data, out.ctypes.data, n_pixels, C, sign_rule), "bitpack")
+    return out
+
+
+def bitpack_i32(x):
+    """x: int32 [..., C] -> uint64 [..., ceil(C/64)], bit = 1 iff x < 0 (Sec. 2.1.1)."""
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    C = x.shape[-1]
+    out = np.empty(x.shape[:-1] + ((C + 63) // 64,), dtype=np.uint64)
+    _check(_load().oracle_bitpack_i32(x.ctypes.data, out.ctypes.data, x.size // C, C), "bitpack_i32")
+    return out
+
+
+def nhwc_to_nc1hwc2(a):
+    """Packed uint64 [N,H,W,Cw] -> [N,ceil(Cw/2),H,W,2] (NC1HWC2 with C2 = 128 bits, Sec. 2.1.2)."""
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    N, H, W, Cw = a.shape
+    out = np.empty((N, (Cw + 1) // 2, H, W, 2), dtype=np.uint64)
+    _check(_load().oracle_nhwc_to_nc1hwc2(a.ctypes.data, out.ctypes.data, N, H, W, Cw), "nhwc_to_nc1hwc2")
     return out
 
 

@@ -216,6 +216,52 @@ int oracle_bconv2d_zeropad(const float *A, const float *Wt, int32_t *Y, int N, i
 }
 
 /*
+ * Bit-packing of int32 tensors (Sec. 2.1.1 uses the sign bit "in int32 and IEEE 754 float"
+ * alike): bit = 1 iff x < 0, same word layout as oracle_bitpack.
+ */
+int oracle_bitpack_i32(const int32_t *x, uint64_t *out, int64_t n_pixels, int C)
+{
+    if (!x || !out || n_pixels < 0 || C <= 0)
+        return ORACLE_BAD_ARG;
+    const int words = (C + 63) / 64;
+    for (int64_t p = 0; p < n_pixels; ++p) {
+        for (int q = 0; q < words; ++q) {
+            uint64_t wd = 0;
+            for (int b = 0; b < 64; ++b) {
+                const int c = 64 * q + b;
+                if (c < C && x[p * C + c] < 0)
+                    wd |= (uint64_t)1 << b;
+            }
+            out[p * words + q] = wd;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * NC1HWC2 layout of Sec. 2.1.2 with C2 = 128 bits (two 64-bit words): the channel words of a
+ * pixel are split into C1 = ceil(Cw/2) groups and the group index becomes the second-slowest
+ * dimension.   in : [N][H][W][Cw]   out : [N][C1][H][W][2]; a missing second word is 0.
+ */
+int oracle_nhwc_to_nc1hwc2(const uint64_t *in, uint64_t *out, int N, int H, int W, int Cw)
+{
+    if (!in || !out || N <= 0 || H <= 0 || W <= 0 || Cw <= 0)
+        return ORACLE_BAD_ARG;
+    const int C1 = (Cw + 1) / 2;
+    for (int n = 0; n < N; ++n)
+        for (int c1 = 0; c1 < C1; ++c1)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int k = 0; k < 2; ++k) {
+                        const int q = 2 * c1 + k;
+                        const uint64_t v =
+                            q < Cw ? in[(((int64_t)n * H + h) * W + w) * Cw + q] : 0;
+                        out[((((int64_t)n * C1 + c1) * H + h) * W + w) * 2 + k] = v;
+                    }
+    return ORACLE_OK;
+}
+
+/*
  * BGEMM (Sec. 2.1.2, Eq. 1) on already-binarized operands.
  *   A : [M][K] values +-1.0f          (row i is the paper's A_{i,.})
  *   B : [N][K] values +-1.0f          (row j is the paper's column B_{.,j})

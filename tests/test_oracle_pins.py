@@ -469,3 +469,38 @@ def test_im2col_bgemm_equals_direct_convolution(oracle, shape):
             assert np.array_equal(row[i * k + j], want)
     g = oracle.bgemm_signed(cols.reshape(cols.shape[0], -1), Wt.reshape(Cout, -1))
     assert np.array_equal(g.reshape(y.shape), y)
+
+
+# ---- int32 bit-packing (Sec. 2.1.1) and the NC1HWC2 layout (Sec. 2.1.2) --------------------------
+
+@pytest.mark.parametrize("C", [1, 63, 64, 65, 130, 256])
+def test_bitpack_i32_matches_numpy_packbits(oracle, C):
+    rng = np.random.default_rng(81 + C)
+    x = rng.integers(-5, 6, size=(7, 3, C)).astype(np.int32)
+    x[0, 0, :] = np.iinfo(np.int32).min
+    x[0, 1, :] = np.iinfo(np.int32).max
+    x[0, 2, :] = 0
+    got = oracle.bitpack_i32(x)
+    pad = (-C) % 64
+    bits = np.pad(x < 0, ((0, 0), (0, 0), (0, pad)))
+    want = np.packbits(bits, axis=-1, bitorder="little").view(np.uint64)
+    assert np.array_equal(got, want.reshape(got.shape))
+    # an int32 and the float of the same sign pack alike, zero included (its sign bit is clear)
+    assert np.array_equal(got, oracle.bitpack(x.astype(np.float32)))
+
+
+@pytest.mark.parametrize("Cw", [1, 2, 3, 8])
+def test_nc1hwc2_is_a_grouped_transpose(oracle, Cw):
+    rng = np.random.default_rng(90 + Cw)
+    a = rng.integers(0, 2**63, size=(2, 3, 5, Cw), dtype=np.uint64)
+    got = oracle.nhwc_to_nc1hwc2(a)
+    C1 = (Cw + 1) // 2
+    padded = np.zeros((2, 3, 5, 2 * C1), np.uint64)
+    padded[..., :Cw] = a
+    want = padded.reshape(2, 3, 5, C1, 2).transpose(0, 3, 1, 2, 4)
+    assert got.shape == (2, C1, 3, 5, 2) and np.array_equal(got, want)
+    # bit c of a pixel sits in group c // 128, at bit c % 128 of that group's two words
+    for c in (0, 63, 64 * Cw - 1):
+        g, b = divmod(c, 128)
+        assert ((got[1, g, 2, 4, b // 64] >> np.uint64(b % 64)) & np.uint64(1)) == \
+               ((a[1, 2, 4, c // 64] >> np.uint64(c % 64)) & np.uint64(1))
