@@ -77,6 +77,24 @@ int dabnn_bitpack(const float *x, uint64_t *out, int64_t n_pixels, int C, int si
                   void *stream);
 
 /*
+ * Sign + bit-pack of an int32 tensor (Sec. 2.1.1: the sign bit of int32 and of IEEE-754 floats is
+ * used alike): bit = 1 iff x < 0.  Same layout, arguments and errors as dabnn_bitpack; useful to
+ * binarize an integer feature map (the output of dabnn_bconv2d) without a float detour.
+ *   x : i32 [n_pixels][C] device        out : u64 [n_pixels][ceil(C/64)] device
+ */
+int dabnn_bitpack_i32(const int32_t *x, uint64_t *out, int64_t n_pixels, int C, void *stream);
+
+/*
+ * Layout conversion between this library's packed NHWC tensors and the paper's NC1HWC2 layout
+ * (Sec. 2.1.2) with C2 = 128 bits, the format daBNN itself stores activations in:
+ *   NHWC    : u64 [N][H][W][Cw]
+ *   NC1HWC2 : u64 [N][C1][H][W][2],  C1 = ceil(Cw/2); for odd Cw the last group's second word is 0
+ * Both device, both below 2^31 words; in and out must not overlap.
+ */
+int dabnn_nhwc_to_nc1hwc2(const uint64_t *in, uint64_t *out, int N, int H, int W, int Cw, void *stream);
+int dabnn_nc1hwc2_to_nhwc(const uint64_t *in, uint64_t *out, int N, int H, int W, int Cw, void *stream);
+
+/*
  * Ahead-of-time packing of binary-convolution weights (Sec. 3), same bit rule as above.
  *   w   : fp32 [Cout][kh][kw][Cin], any values (only the sign is used), read only
  *   out : u64  [Cout][kh][kw][ceil(Cin/64)]   -- the canonical packed weight layout

@@ -41,6 +41,9 @@ def load():
     lib.dabnn_bconv2d_algo.argtypes, lib.dabnn_bconv2d_algo.restype = [vp] * 3 + [i32] * 10 + [vp], i32
     lib.dabnn_bgemm.argtypes, lib.dabnn_bgemm.restype = [vp] * 3 + [i64, i32, i32, i32, i32, vp], i32
     lib.dabnn_im2col.argtypes, lib.dabnn_im2col.restype = [vp] * 2 + [i32] * 8 + [vp], i32
+    lib.dabnn_bitpack_i32.argtypes, lib.dabnn_bitpack_i32.restype = [vp, vp, i64, i32, vp], i32
+    for f in (lib.dabnn_nhwc_to_nc1hwc2, lib.dabnn_nc1hwc2_to_nhwc):
+        f.argtypes, f.restype = [vp, vp] + [i32] * 4 + [vp], i32
     lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
     lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
@@ -56,7 +59,8 @@ def load():
 EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_pack_weights",
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
            "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
-           "dabnn_expand_int8", "dabnn_bconv2d_int8"]
+           "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
+           "dabnn_nc1hwc2_to_nhwc"]
 
 
 def status_string(status):
@@ -176,6 +180,37 @@ def im2col(a, Cin, kh, kw, stride=1, pad=0, out=None):
         out = torch.empty((N * Ho * Wo, kh * kw * Cw), dtype=torch.int64, device=a.device)
     _check(load().dabnn_im2col(_dev(a, torch.int64, "a"), _dev(out, torch.int64, "out"), N, H, W, Cin,
                                kh, kw, stride, pad, _stream()), "dabnn_im2col")
+    return out
+
+
+def bitpack_i32(x, out=None):
+    """x: int32 [..., C] -> int64 [..., ceil(C/64)], bit = 1 iff x < 0."""
+    C = x.shape[-1]
+    n_pixels = x.numel() // C if C else 0
+    if out is None:
+        out = torch.empty(tuple(x.shape[:-1]) + ((C + 63) // 64,), dtype=torch.int64, device=x.device)
+    _check(load().dabnn_bitpack_i32(_dev(x, torch.int32, "x"), _dev(out, torch.int64, "out"), n_pixels, C,
+                                    _stream()), "dabnn_bitpack_i32")
+    return out
+
+
+def nhwc_to_nc1hwc2(a):
+    """Packed int64 [N,H,W,Cw] -> [N,ceil(Cw/2),H,W,2] (C2 = 128 bits)."""
+    N, H, W, Cw = a.shape
+    out = torch.empty((N, (Cw + 1) // 2, H, W, 2), dtype=torch.int64, device=a.device)
+    _check(load().dabnn_nhwc_to_nc1hwc2(_dev(a, torch.int64, "a"), _dev(out, torch.int64, "out"), N, H, W,
+                                        Cw, _stream()), "dabnn_nhwc_to_nc1hwc2")
+    return out
+
+
+def nc1hwc2_to_nhwc(g, Cw):
+    """Inverse of nhwc_to_nc1hwc2 for a tensor of Cw words per pixel."""
+    N, C1, H, W, two = g.shape
+    if two != 2 or C1 != (Cw + 1) // 2:
+        raise ValueError("not an NC1HWC2 tensor of that channel count")
+    out = torch.empty((N, H, W, Cw), dtype=torch.int64, device=g.device)
+    _check(load().dabnn_nc1hwc2_to_nhwc(_dev(g, torch.int64, "g"), _dev(out, torch.int64, "out"), N, H, W,
+                                        Cw, _stream()), "dabnn_nc1hwc2_to_nhwc")
     return out
 
 

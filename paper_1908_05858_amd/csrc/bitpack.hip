@@ -82,7 +82,47 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_kernel(
         out[g0 + lane] = make_uint2(lo, hi);
 }
 
+// NHWC words -> NC1HWC2 with C2 = 128 bits (Sec. 2.1.2): one thread per 16-byte group of the
+// output, so stores are fully coalesced; reads are two adjacent words of a pixel.
+__global__ __launch_bounds__(256) void nc1hwc2_kernel(const uint64_t* __restrict__ in,
+                                                      uint2* __restrict__ out_words, int64_t total,
+                                                      int HW, int Cw, int C1, bool to_grouped)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;  // (n, c1, hw)
+    if (idx >= total)
+        return;
+    const int hw = static_cast<int>(idx % HW);
+    const int64_t t = idx / HW;
+    const int c1 = static_cast<int>(t % C1);
+    const int64_t n = t / C1;
+    const int64_t nhwc = (n * HW + hw) * Cw + 2 * c1;  // first word of the group in NHWC order
+    uint64_t* outw = reinterpret_cast<uint64_t*>(out_words);
+    if (to_grouped) {
+        const uint64_t w0 = in[nhwc];
+        const uint64_t w1 = (2 * c1 + 1 < Cw) ? in[nhwc + 1] : 0;  // a missing second word is 0
+        outw[2 * idx] = w0;
+        outw[2 * idx + 1] = w1;
+    } else {
+        outw[nhwc] = in[2 * idx];
+        if (2 * c1 + 1 < Cw)
+            outw[nhwc + 1] = in[2 * idx + 1];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_nc1hwc2(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw,
+                          bool to_grouped, hipStream_t stream)
+{
+    const int C1 = (Cw + 1) / 2;
+    const int64_t total = static_cast<int64_t>(N) * C1 * H * W;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL)
+        return hipErrorInvalidValue;
+    nc1hwc2_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream>>>(
+        in, reinterpret_cast<uint2*>(out), total, H * W, Cw, C1, to_grouped);
+    return hipGetLastError();
+}
 
 hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, int sign_mode,
                           hipStream_t stream)

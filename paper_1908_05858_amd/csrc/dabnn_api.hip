@@ -99,6 +99,37 @@ int dabnn_bitpack(const float* x, uint64_t* out, int64_t n_pixels, int C, int si
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
+int dabnn_bitpack_i32(const int32_t* x, uint64_t* out, int64_t n_pixels, int C, void* stream)
+{
+    // The sign bit of an int32 is bit 31, like that of an fp32: the same kernel on the raw bits.
+    return dabnn_bitpack(reinterpret_cast<const float*>(x), out, n_pixels, C, DABNN_SIGN_BIT, stream);
+}
+
+static int layout_call(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw, bool to_grouped,
+                       void* stream)
+{
+    if (!in || !out)
+        return DABNN_ERR_NULL;
+    if (N <= 0 || H <= 0 || W <= 0 || Cw <= 0 ||
+        static_cast<int64_t>(N) * H * W * (Cw + 1) > kMaxElems)
+        return DABNN_ERR_SHAPE;
+    if (!aligned(in, 8) || !aligned(out, 8))
+        return DABNN_ERR_ALIGN;
+    const hipError_t e =
+        dabnn::launch_nc1hwc2(in, out, N, H, W, Cw, to_grouped, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_nhwc_to_nc1hwc2(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw, void* stream)
+{
+    return layout_call(in, out, N, H, W, Cw, true, stream);
+}
+
+int dabnn_nc1hwc2_to_nhwc(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw, void* stream)
+{
+    return layout_call(in, out, N, H, W, Cw, false, stream);
+}
+
 int dabnn_pack_weights(const float* w, uint64_t* out, int Cout, int kh, int kw, int Cin,
                        int sign_mode, void* stream)
 {

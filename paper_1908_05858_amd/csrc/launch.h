@@ -16,6 +16,10 @@ struct ConvShape {
 hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, int sign_mode,
                           hipStream_t stream);
 
+// Packed NHWC [N][H][W][Cw] <-> NC1HWC2 [N][ceil(Cw/2)][H][W][2] (Sec. 2.1.2, C2 = 128 bits).
+hipError_t launch_nc1hwc2(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw,
+                          bool to_grouped, hipStream_t stream);
+
 // Binary convolution kernels (Sec. 2.1.2, Eq. 6-7).  Each returns hipErrorNotSupported, without
 // launching, when the family cannot run the shape.
 hipError_t launch_bconv_reference(const uint64_t* a, const uint64_t* w, int32_t* y,

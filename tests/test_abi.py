@@ -170,3 +170,16 @@ def test_int8_route_bad_arguments(lib):
     assert lib.dabnn_bconv2d_int8(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
     assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 80, 64, 3, 3, 1, 1, None) == 4
     assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 64, 48, 3, 3, 1, 1, None) == 4
+
+
+def test_layout_and_int32_pack_bad_arguments(lib):
+    P = ctypes.c_void_p
+    a, o = P(0x10000), P(0x20000)
+    assert lib.dabnn_bitpack_i32(a, P(0), 4, 64, None) == 1
+    assert lib.dabnn_bitpack_i32(a, o, 4, 0, None) == 2
+    assert lib.dabnn_bitpack_i32(P(0x10002), o, 4, 64, None) == 3
+    assert lib.dabnn_bitpack_i32(P(0), P(0), 0, 64, None) == 0
+    for f in (lib.dabnn_nhwc_to_nc1hwc2, lib.dabnn_nc1hwc2_to_nhwc):
+        assert f(a, P(0), 1, 2, 2, 3, None) == 1
+        assert f(a, o, 1, 0, 2, 3, None) == 2
+        assert f(a, P(0x20004), 1, 2, 2, 3, None) == 3

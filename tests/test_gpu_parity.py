@@ -72,6 +72,34 @@ def test_bitpack_empty(dabnn):
     assert dabnn.bitpack(x).shape == (0, 1)
 
 
+@pytest.mark.parametrize("C", [1, 64, 65, 200, 512])
+def test_bitpack_i32(dabnn, oracle, C):
+    rng = np.random.default_rng(300 + C)
+    x = rng.integers(-1000, 1000, size=(3, 37, C)).astype(np.int32)
+    x[0, 0, :] = np.iinfo(np.int32).min
+    x[0, 1, :] = 0
+    assert np.array_equal(words(dabnn.bitpack_i32(gpu(x))), oracle.bitpack_i32(x))
+
+
+def test_bitpack_i32_binarizes_a_conv_output(dabnn, oracle):
+    x = wl.activations((2, 14, 14, 64), 311)
+    wf = wl.weights((128, 3, 3, 64), 312)
+    y = dabnn.bconv2d(dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf)), 64, 1, 1)
+    assert np.array_equal(words(dabnn.bitpack_i32(y)), oracle.bitpack_i32(oracle.bconv2d(x, wf, 1, 1)))
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 5, 7, 2), (3, 9, 4, 3), (2, 14, 14, 8), (1, 3, 3, 5)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_nc1hwc2_round_trip(dabnn, oracle, shape):
+    rng = np.random.default_rng(sum(shape))
+    a = rng.integers(0, 2**63, size=shape, dtype=np.uint64)
+    a_gpu = gpu(a.view(np.int64))
+    g = dabnn.nhwc_to_nc1hwc2(a_gpu)
+    assert np.array_equal(words(g), oracle.nhwc_to_nc1hwc2(a))
+    back = dabnn.nc1hwc2_to_nhwc(g, shape[3])
+    assert torch.equal(back, a_gpu)
+
+
 def test_pack_weights(dabnn, oracle):
     for shape in [(64, 3, 3, 64), (128, 3, 3, 80), (5, 1, 1, 200), (7, 5, 5, 3), (512, 3, 3, 512)]:
         w = wl.weights(shape, 77 + shape[0], p_plus=0.3)
