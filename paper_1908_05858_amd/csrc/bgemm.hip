@@ -16,6 +16,8 @@
 namespace dabnn {
 namespace {
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+
 // acc[q] += popcount(w_q[0] ^ a0) + popcount(w_q[1] ^ a1) for four rows q of B.  w in SGPRs that
 // only scalar loads write (see the note in bconv_areg.hip), a in VGPRs.
 template <bool FIRST>
@@ -66,11 +68,11 @@ __device__ __forceinline__ void xor_popc_4x2(int* acc, uint32_t a0, uint32_t a1,
 #undef DABNN_INPUTS
 }
 
-// A group = 16 rows of B against one 64-row tile of A.  Its scalar loads go through a
+// A group = CG (16 or 32) rows of B against one 64-row tile of A.  Its scalar loads go through a
 // double-buffered pipeline in units of CU rows of B x DU dwords (at most 24 SGPRs per buffer: two buffers plus the loop state must fit the SGPR file without spills).
-template <int KD>
+template <int KD, int CGC>
 struct GemmGeom {
-    static constexpr int CG = 16;
+    static constexpr int CG = CGC;
     static constexpr int DU = KD % 6 == 0 ? 6 : (KD % 4 == 0 ? 4 : 2);
     static constexpr int CU = DU == 2 ? 8 : 4;
     static constexpr int SB = CU * DU;
@@ -78,11 +80,11 @@ struct GemmGeom {
     static constexpr int UNITS = (CG / CU) * CHUNKS;  // units per group (even)
 };
 
-template <int KD, int UNIT, int SB>
+template <int KD, int CGC, int UNIT, int SB>
 __device__ __forceinline__ void gemm_load_unit(uint32_t (&sb)[SB], const uint32_t* __restrict__ b,
                                                int row0)
 {
-    using G = GemmGeom<KD>;
+    using G = GemmGeom<KD, CGC>;
     constexpr int part = UNIT / G::CHUNKS;
     constexpr int chunk = UNIT % G::CHUNKS;
     const uint32_t* src = b + static_cast<size_t>(row0 + G::CU * part) * KD + chunk * G::DU;
@@ -94,11 +96,11 @@ __device__ __forceinline__ void gemm_load_unit(uint32_t (&sb)[SB], const uint32_
     }
 }
 
-template <int KD, int UNIT, int SB>
-__device__ __forceinline__ void gemm_compute_unit(const uint32_t (&sb)[SB], int (&acc)[16],
+template <int KD, int CGC, int UNIT, int SB>
+__device__ __forceinline__ void gemm_compute_unit(const uint32_t (&sb)[SB], int (&acc)[CGC],
                                                   const uint32_t (&areg)[KD])
 {
-    using G = GemmGeom<KD>;
+    using G = GemmGeom<KD, CGC>;
     constexpr int part = UNIT / G::CHUNKS;
     constexpr int chunk = UNIT % G::CHUNKS;
 #pragma unroll
@@ -113,14 +115,14 @@ __device__ __forceinline__ void gemm_compute_unit(const uint32_t (&sb)[SB], int 
     }
 }
 
-template <int KD>
+template <int KD, int CGC>
 __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
     const uint32_t* __restrict__ A, const uint32_t* __restrict__ B, int32_t* __restrict__ C, int M,
     int N, int K, int neg_scale, int groups_per_tile, int n_ranges, int base_groups, int rem_groups)
 {
-    using G = GemmGeom<KD>;
+    using G = GemmGeom<KD, CGC>;
     static_assert(G::UNITS % 2 == 0 && KD % G::DU == 0 && G::DU % 2 == 0, "pipeline geometry");
-    __shared__ int32_t tile_lds[4 * 64 * 16];  // 64 rows x 16 columns of int32 per wavefront
+    __shared__ int32_t tile_lds[4 * 64 * CGC];  // 64 rows x CG columns of int32 per wavefront
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
     load_rows(tile);
 
     uint32_t sb0[G::SB], sb1[G::SB];
-    gemm_load_unit<KD, 0>(sb0, B, cgi * G::CG);
+    gemm_load_unit<KD, CGC, 0>(sb0, B, cgi * G::CG);
 
     for (; g < g_end; ++g) {
         int ncgi = cgi + 1, ntile = tile;
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
             ncgi = 0;
             ++ntile;
         }
-        int acc[16];
+        int acc[CGC];
         // Software pipeline: while unit u feeds the VALU, unit u+1 is in flight.
         static_for<0, G::UNITS>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
@@ -177,38 +179,42 @@ __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
             schedule_fence();
             if constexpr (u + 1 < G::UNITS) {
                 if constexpr (u % 2 == 0)
-                    gemm_load_unit<KD, u + 1>(sb1, B, cgi * G::CG);
+                    gemm_load_unit<KD, CGC, u + 1>(sb1, B, cgi * G::CG);
                 else
-                    gemm_load_unit<KD, u + 1>(sb0, B, cgi * G::CG);
+                    gemm_load_unit<KD, CGC, u + 1>(sb0, B, cgi * G::CG);
             } else {
                 if (g + 1 < g_end)  // first unit of the next group (UNITS is even: buffer 0)
-                    gemm_load_unit<KD, 0>(sb0, B, ncgi * G::CG);
+                    gemm_load_unit<KD, CGC, 0>(sb0, B, ncgi * G::CG);
             }
             schedule_fence();
             if constexpr (u % 2 == 0)
-                gemm_compute_unit<KD, u>(sb0, acc, areg);
+                gemm_compute_unit<KD, CGC, u>(sb0, acc, areg);
             else
-                gemm_compute_unit<KD, u>(sb1, acc, areg);
+                gemm_compute_unit<KD, CGC, u>(sb1, acc, areg);
             schedule_fence();
         });
 
-        // Row P of the wavefront's LDS slice holds row P's 16 results as four 16-byte quads; quad
+        // Row P of the wavefront's LDS slice holds row P's CG results as QPR 16-byte quads; quad
         // j sits in column j ^ swz(P), which keeps both the row-wise writes and the transposed
-        // reads free of bank conflicts.  Four neighbouring lanes then store the 64 contiguous
-        // bytes of one row of C.
-        auto swz = [](int P) { return (P >> 1) & 3; };
-        int32_t* slice = tile_lds + wave * (64 * 16);
+        // reads free of bank conflicts (a 64-byte row covers half the banks, so two neighbouring
+        // rows share one swizzle; a 128-byte row covers all of them).  QPR neighbouring lanes
+        // then store the 64 or 128 contiguous bytes of one row of C, non-temporally: C is
+        // written once and never read here.
+        constexpr int QPR = CGC / 4;    // quads per row = lanes per row in the transposed store
+        constexpr int PPI = 64 / QPR;   // rows per store instruction
+        auto swz = [](int P) { return (CGC == 16) ? ((P >> 1) & 3) : (P & 7); };
+        int32_t* slice = tile_lds + wave * (64 * CGC);
         {
             const int sw = swz(lane);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < QPR; ++j) {
                 int4 o;
                 // K - 2d (dot product) or K - d (match count), d < 2^23
                 o.x = K + __mul24(neg_scale, acc[4 * j + 0]);
                 o.y = K + __mul24(neg_scale, acc[4 * j + 1]);
                 o.z = K + __mul24(neg_scale, acc[4 * j + 2]);
                 o.w = K + __mul24(neg_scale, acc[4 * j + 3]);
-                *reinterpret_cast<int4*>(slice + lane * 16 + 4 * (j ^ sw)) = o;
+                *reinterpret_cast<int4*>(slice + lane * CGC + 4 * (j ^ sw)) = o;
             }
         }
         // LDS instructions of one wavefront execute in order; this only stops the compiler from
@@ -216,14 +222,17 @@ __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int j = lane & 3;
+        const int j = lane % QPR;
         char* dst = reinterpret_cast<char*>(C + static_cast<size_t>(tile) * 64 * N + cgi * G::CG);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int P = 16 * k + (lane >> 2);
-            const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ swz(P)));
-            if (tile * 64 + P < M)
-                *reinterpret_cast<int4*>(dst + (static_cast<uint32_t>(P) * N + 4 * j) * 4u) = o;
+        for (int k = 0; k < QPR; ++k) {
+            const int P = PPI * k + lane / QPR;
+            const int4 o = *reinterpret_cast<const int4*>(slice + P * CGC + 4 * (j ^ swz(P)));
+            if (tile * 64 + P < M) {
+                v4i v = {o.x, o.y, o.z, o.w};
+                __builtin_nontemporal_store(
+                    v, reinterpret_cast<v4i*>(dst + (static_cast<uint32_t>(P) * N + 4 * j) * 4u));
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -235,14 +244,14 @@ __global__ __launch_bounds__(256) void bgemm_rowreg_kernel(
     }
 }
 
-template <int KD>
-hipError_t launch_rowreg(const uint32_t* A, const uint32_t* B, int32_t* C, int64_t M, int N, int K,
-                         int mode, hipStream_t stream)
+template <int KD, int CGC>
+hipError_t launch_rowreg_cg(const uint32_t* A, const uint32_t* B, int32_t* C, int64_t M, int N, int K,
+                            int mode, hipStream_t stream)
 {
-    auto kernel = bgemm_rowreg_kernel<KD>;
+    auto kernel = bgemm_rowreg_kernel<KD, CGC>;
     static const int blocks_per_cu = resident_blocks_per_cu(kernel);
     const int64_t tiles = (M + 63) / 64;
-    const int groups_per_tile = N / 16;
+    const int groups_per_tile = N / CGC;
     const int64_t n_groups64 = tiles * groups_per_tile;
     if (n_groups64 > 0x3fffffff)
         return hipErrorNotSupported;
@@ -257,6 +266,19 @@ hipError_t launch_rowreg(const uint32_t* A, const uint32_t* B, int32_t* C, int64
                        mode == 1 ? -1 : -2, groups_per_tile, n_ranges, n_groups / n_ranges,
                        n_groups % n_ranges);
     return hipGetLastError();
+}
+
+template <int KD>
+hipError_t launch_rowreg(const uint32_t* A, const uint32_t* B, int32_t* C, int64_t M, int N, int K,
+                         int mode, hipStream_t stream)
+{
+    // With short rows the product is bound by the int32 output: 32 columns per group make every
+    // store a whole 128-byte line.  Long rows keep 16 columns (fewer registers, finer work split).
+    if constexpr (KD <= 16) {
+        if (N % 32 == 0 && env_int("DABNN_BGEMM_CG", 32) == 32)  // test hook: force 16 columns
+            return launch_rowreg_cg<KD, 32>(A, B, C, M, N, K, mode, stream);
+    }
+    return launch_rowreg_cg<KD, 16>(A, B, C, M, N, K, mode, stream);
 }
 
 // ------------------------------------------------------------------------------ reference

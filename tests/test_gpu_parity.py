@@ -304,6 +304,17 @@ def test_bgemm(dabnn, oracle, shape, mode):
     assert np.array_equal(C.cpu().numpy(), want)
 
 
+def test_bgemm_sixteen_column_groups_forced(dabnn, oracle, monkeypatch):
+    """Short rows default to 32-column groups (whole 128-byte stores); the 16-column kernel of the
+    same shapes through the library's test hook."""
+    monkeypatch.setenv("DABNN_BGEMM_CG", "16")
+    for M, N, K in [(200, 64, 64), (1000, 32, 128), (300, 128, 512), (4100, 256, 64)]:
+        xa = wl.activations((M, K), 883 + M)
+        xb = wl.weights((N, K), 884 + K)
+        C = dabnn.bgemm(dabnn.bitpack(gpu(xa)), dabnn.bitpack(gpu(xb)), K)
+        assert np.array_equal(C.cpu().numpy(), oracle.bgemm_signed(oracle.sign(xa), oracle.sign(xb)))
+
+
 IM2COL_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
     (2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 32, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
     (2, 7, 7, 512, 64, 3, 1, 1), (1, 10, 17, 200, 33, 3, 2, 1), (1, 12, 12, 64, 16, 5, 1, 2),
