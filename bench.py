@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per step (16 launches) at batch 256, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) scaled by a plain 1 GiB copy; see profiles/bench_bireal18_b256_hbm_traffic.md.
 # Algorithmic: conv 1.597e9 (56 MB read + 1541 MB written), bit-pack 1.775e9.
-MEASURED_TRAFFIC_B256 = {"bconv": 1.937e9, "bitpack": 1.776e9}
+MEASURED_TRAFFIC_B256 = {"bconv": 1.947e9, "bitpack": 1.776e9}
 
 
 def main():
