@@ -4,7 +4,10 @@ Bi-Real-Net-18 body at 224x224 input, batch 256, each preceded by the bit-pack o
 activation.  One step = 16 x (dabnn_bitpack + dabnn_bconv2d) over inputs resident in HBM.
 
 Prints ONE JSON line.  `value` is binary-convolution GOPS (2*K*Cout*Ho*Wo*N summed over the 16
-layers, divided by the wall time of a whole step, bit-packing included).
+layers, divided by the wall time of a whole step, bit-packing included).  After the headline
+region the same layers are timed through two widened entry points, reported beside it and never
+in it: `fused_bnsign` (conv + BN threshold + bit-pack in one kernel) and `int8_mfma_comparison`
+(bits expanded to +-1 bytes, int8 matrix cores).
 """
 import argparse
 import json

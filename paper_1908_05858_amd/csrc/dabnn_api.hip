@@ -1,5 +1,7 @@
 // C ABI of the library (see include/dabnn.h): argument validation, error codes, dispatch.
-// Nothing here computes; every step of the path runs in the kernels of bitpack.hip / bconv.hip.
+// Nothing here computes, with one host-side exception (dabnn_bn_thresholds, which turns batch-norm
+// parameters into integer thresholds); every device step runs in the kernels of bitpack.hip,
+// bconv*.hip and bgemm.hip.
 #include "../../include/dabnn.h"
 
 #include "launch.h"
