@@ -536,3 +536,60 @@ def test_cfg5_full_batch_layers(dabnn, oracle, li):
         assert np.array_equal(y_gpu[n:n + 1], oracle.bconv2d_signed(A[n:n + 1], Wt, L.stride, 1))
     # properties that hold at any size: parity of K and the bound |y| <= K
     assert np.all((y_gpu - L.K) % 2 == 0) and np.abs(y_gpu).max() <= L.K
+
+
+# ------------------------------------------------------------------------ streams and HIP graphs
+
+def test_calls_follow_the_current_stream(dabnn, oracle):
+    """The binding passes torch's current stream; work enqueued on a side stream must be ordered
+    after that stream's earlier work and produce the same result."""
+    x = wl.activations((4, 28, 28, 128), 4101)
+    wf = wl.weights((128, 3, 3, 128), 4102)
+    xg, wg = gpu(x), gpu(wf)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        a = dabnn.bitpack(xg)
+        y = dabnn.bconv2d(a, dabnn.pack_weights(wg), 128, 1, 1)
+    side.synchronize()
+    assert np.array_equal(y.cpu().numpy(), oracle.bconv2d(x, wf, 1, 1))
+
+
+def test_hip_graph_replay_of_the_hot_path(dabnn, oracle):
+    """The entry points neither allocate nor synchronise, so bit-pack + conv (+ the fused and the
+    zero-padded variants) can be captured into a HIP graph; every replay, with the input changed
+    by eager work in between, must equal the oracle."""
+    N, H, W, Cin, Cout = 3, 14, 14, 128, 128
+    wf = wl.weights((Cout, 3, 3, Cin), 4202)
+    wp = dabnn.pack_weights(gpu(wf))
+    gamma, beta, mean, var = _bn_params(Cout, 4203)
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * Cin)
+    xg = torch.empty((N, H, W, Cin), dtype=torch.float32, device="cuda")
+    a = torch.empty((N, H, W, Cin // 64), dtype=torch.int64, device="cuda")
+    y = torch.empty((N, H, W, Cout), dtype=torch.int32, device="cuda")
+    y0 = torch.empty_like(y)
+    bits = torch.empty((N, H, W, Cout // 64), dtype=torch.int64, device="cuda")
+
+    def enqueue():
+        dabnn.bitpack(xg, out=a)
+        dabnn.bconv2d(a, wp, Cin, 1, 1, out=y)
+        dabnn.bconv2d_zeropad(a, wp, Cin, 1, 1, out=y0)
+        dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, 1, 1, out=bits)
+
+    xg.copy_(gpu(wl.activations((N, H, W, Cin), 4200)))
+    enqueue()  # eager once: one-time occupancy queries happen outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(4):
+        x = wl.activations((N, H, W, Cin), 4210 + rep)
+        xg.copy_(gpu(x))          # eager work between the replays
+        y.zero_(); y0.zero_(); bits.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(words(a), oracle.bitpack(x)), rep
+        assert np.array_equal(y.cpu().numpy(), oracle.bconv2d(x, wf, 1, 1)), rep
+        assert np.array_equal(y0.cpu().numpy(), oracle.bconv2d_zeropad(x, wf, 1, 1)), rep
+        assert np.array_equal(words(bits), oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, 1, 1)), rep
