@@ -184,6 +184,30 @@ def main():
         mfma_conv_ms = (time.perf_counter() - t5) * 1e3 / k_cmp
         del w8s, a8s
 
+    # The largest bit-pack shape of the parity configs (benchmark configs[2]: 256x56x56x256,
+    # 822 MB of fp32), far beyond the 256 MB Infinity Cache: the launch the HBM fraction of the
+    # bit-pack kernel is claimed on.  One HIP-event pair per launch.
+    big = None
+    if N == wl.CFG5_BATCH:
+        shape = wl.CFG3_SHAPES[2]
+        xb = torch.empty(shape, dtype=torch.float32, device="cuda").normal_()
+        ob = torch.empty(shape[:-1] + ((shape[-1] + 63) // 64,), dtype=torch.int64, device="cuda")
+        binding.bitpack(xb, out=ob)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for e0, e1 in evs:
+            e0.record()
+            binding.bitpack(xb, out=ob)
+            e1.record()
+        torch.cuda.synchronize()
+        us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
+        moved = xb.numel() * 4 + ob.numel() * 8
+        big = {"shape": "x".join(map(str, shape)), "MB_moved": round(moved / 1e6, 1),
+               "median_us": round(us[len(us) // 2], 2), "min_us": round(us[0], 2),
+               "GBps_median": round(moved / us[len(us) // 2] / 1e3, 1),
+               "frac_of_hbm_peak": round(moved / us[len(us) // 2] / 1e3 / HBM_PEAK_GBPS, 4)}
+        del xb, ob
+
     ops = [L.ops(N) for L in layers]
     total_ops = float(sum(ops))
     pack_bytes = [xs[li].numel() * 4 + acts[li].numel() * 8 for li in range(len(layers))]
@@ -248,6 +272,8 @@ def main():
         },
         "per_layer": per_layer,
     }
+    if big is not None:
+        result["roofline_bitpack"]["largest_launch"] = big
     if mfma_ms is not None:
         result["int8_mfma_comparison"] = {
             "what": "16 x (dabnn_expand_int8 of the packed activations + dabnn_bconv2d_int8 on "
