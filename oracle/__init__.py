@@ -35,7 +35,7 @@ def build(force=False):
     """Compile the oracle with gcc.  AVX2 baseline so one build runs on any host of this pool."""
     if not force and os.path.exists(_LIB_PATH) and os.path.getmtime(_LIB_PATH) >= os.path.getmtime(_SRC):
         return _LIB_PATH
-    cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fno-fast-math", "-std=c11", "-Wall",
+    cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-std=c11", "-Wall",
            "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB_PATH, "-lm"]
     subprocess.run(cmd, check=True)
     return _LIB_PATH
@@ -55,6 +55,7 @@ def _load():
     lib.oracle_bconv2d_zeropad.argtypes = [vp, vp, vp] + [i32] * 9
     lib.oracle_bitpack_i32.argtypes = [vp, vp, i64, i32]
     lib.oracle_nhwc_to_nc1hwc2.argtypes = [vp, vp] + [i32] * 4
+    lib.oracle_bn_sign_pack.argtypes = [vp] * 6 + [i64, i32]
     lib.oracle_bgemm.argtypes = [vp, vp, vp, i64, i32, i32, i32]
     lib.oracle_bconv2d_at.argtypes = [vp, vp, vp, i64, vp] + [i32] * 9
     lib.oracle_glue.argtypes = [vp] * 5 + [i32] * 9
@@ -62,7 +63,7 @@ def _load():
     for f in (lib.oracle_sign, lib.oracle_bitpack, lib.oracle_conv_out_dim, lib.oracle_bconv2d,
               lib.oracle_bconv2d_at, lib.oracle_glue, lib.oracle_bconv2d_bnsign,
               lib.oracle_bconv2d_zeropad, lib.oracle_bgemm, lib.oracle_bitpack_i32,
-              lib.oracle_nhwc_to_nc1hwc2):
+              lib.oracle_nhwc_to_nc1hwc2, lib.oracle_bn_sign_pack):
         f.restype = i32
     _lib = lib
     return lib
@@ -112,6 +113,28 @@ def nhwc_to_nc1hwc2(a):
     out = np.empty((N, (Cw + 1) // 2, H, W, 2), dtype=np.uint64)
     _check(_load().oracle_nhwc_to_nc1hwc2(a.ctypes.data, out.ctypes.data, N, H, W, Cw), "nhwc_to_nc1hwc2")
     return out
+
+
+def bn_sign_pack(y, scale, shift, r=None, want_x=True):
+    """Fused BN + (shortcut) + sign + pack in fp32, every operation rounded separately:
+    z = (scale*y + shift) + r.  y: int32 [..., C] -> (z float32 [..., C] or None, bits uint64
+    [..., ceil(C/64)])  (Sec. 2.1.1 fused BN-binarization; Sec. 2.3 Bi-Real shortcut)."""
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    scale, shift = _f32(scale), _f32(shift)
+    C = y.shape[-1]
+    if scale.shape != (C,) or shift.shape != (C,):
+        raise ValueError("scale/shift must have shape (C,)")
+    if r is not None:
+        r = _f32(r)
+        if r.shape != y.shape:
+            raise ValueError("shortcut shape differs")
+    x = np.empty(y.shape, np.float32) if want_x else None
+    bits = np.empty(y.shape[:-1] + ((C + 63) // 64,), dtype=np.uint64)
+    _check(_load().oracle_bn_sign_pack(y.ctypes.data, scale.ctypes.data, shift.ctypes.data,
+                                       r.ctypes.data if r is not None else None,
+                                       x.ctypes.data if x is not None else None, bits.ctypes.data,
+                                       y.size // C, C), "bn_sign_pack")
+    return x, bits
 
 
 def conv_out_dim(size, k, stride, pad):

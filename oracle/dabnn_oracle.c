@@ -262,6 +262,42 @@ int oracle_nhwc_to_nc1hwc2(const uint64_t *in, uint64_t *out, int N, int H, int 
 }
 
 /*
+ * Fused batch-norm + binarization layer between two binary convolutions (Sec. 2.1.1, last
+ * sentence, names the layer; Sec. 2.3 benchmarks Bi-Real Net 18, whose blocks add a real-valued
+ * shortcut before the next sign).  Reading taken, in IEEE single precision with every operation
+ * rounded separately (no fused multiply-add):
+ *
+ *   z[p,c] = ((scale[c] * (float)y[p,c]) + shift[c]) + r[p,c]        (r omitted when NULL)
+ *   bit    = IEEE sign bit of z                                      (Sec. 2.1.1 sign rule)
+ *
+ * y is the integer convolution output, scale/shift the folded batch-norm.  z is written to
+ * x_out when that is not NULL (the next block's shortcut); bits are packed like everywhere else.
+ */
+int oracle_bn_sign_pack(const int32_t *y, const float *scale, const float *shift, const float *r,
+                        float *x_out, uint64_t *bits, int64_t n_pixels, int C)
+{
+    if (!y || !scale || !shift || !bits || n_pixels < 0 || C <= 0)
+        return ORACLE_BAD_ARG;
+    const int words = (C + 63) / 64;
+    for (int64_t p = 0; p < n_pixels; ++p) {
+        for (int q = 0; q < words; ++q)
+            bits[p * words + q] = 0;
+        for (int c = 0; c < C; ++c) {
+            volatile float t = scale[c] * (float)y[p * C + c];  /* volatile: each step rounded */
+            t = t + shift[c];
+            if (r)
+                t = t + r[p * C + c];
+            const float z = t;
+            if (x_out)
+                x_out[p * C + c] = z;
+            if (signbit(z))
+                bits[p * words + c / 64] |= (uint64_t)1 << (c % 64);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * BGEMM (Sec. 2.1.2, Eq. 1) on already-binarized operands.
  *   A : [M][K] values +-1.0f          (row i is the paper's A_{i,.})
  *   B : [N][K] values +-1.0f          (row j is the paper's column B_{.,j})

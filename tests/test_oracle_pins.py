@@ -504,3 +504,45 @@ def test_nc1hwc2_is_a_grouped_transpose(oracle, Cw):
         g, b = divmod(c, 128)
         assert ((got[1, g, 2, 4, b // 64] >> np.uint64(b % 64)) & np.uint64(1)) == \
                ((a[1, 2, 4, c // 64] >> np.uint64(c % 64)) & np.uint64(1))
+
+
+# ---- fused BN + shortcut + sign + pack layer (Sec. 2.1.1 last sentence; Sec. 2.3 Bi-Real) --------
+
+@pytest.mark.parametrize("C", [1, 64, 80, 200])
+@pytest.mark.parametrize("with_r", [False, True])
+def test_bn_sign_pack_against_numpy_float32(oracle, C, with_r):
+    """numpy evaluates float32 expressions one rounded operation at a time, without fused
+    multiply-add: the same arithmetic, written independently."""
+    rng = np.random.default_rng(500 + C + with_r)
+    y = rng.integers(-576, 577, size=(3, 11, C)).astype(np.int32)
+    scale = rng.uniform(-0.2, 0.2, C).astype(np.float32)
+    scale[::5] = 0.0
+    shift = rng.normal(0, 1, C).astype(np.float32)
+    r = rng.normal(0, 2, y.shape).astype(np.float32) if with_r else None
+    x, bits = oracle.bn_sign_pack(y, scale, shift, r)
+    z = scale * y.astype(np.float32)
+    assert z.dtype == np.float32
+    z = z + shift
+    if with_r:
+        z = z + r
+    assert np.array_equal(x.view(np.uint32), z.view(np.uint32))          # bit for bit, -0.0 included
+    assert np.array_equal(bits, oracle.bitpack(z))                        # sign rule of Sec. 2.1.1
+    # the fp64 value agrees to float32 rounding, so no term was dropped or mis-signed
+    z64 = scale.astype(np.float64) * y + shift + (r if with_r else 0.0)
+    assert np.allclose(x, z64, rtol=0, atol=1e-4)
+    assert oracle.bn_sign_pack(y, scale, shift, r, want_x=False)[0] is None
+
+
+def test_bn_sign_pack_closed_forms(oracle):
+    C = 70
+    y = np.tile(np.arange(-35, 35, dtype=np.int32), (2, 1))
+    one, zero = np.ones(C, np.float32), np.zeros(C, np.float32)
+    x, bits = oracle.bn_sign_pack(y, one, zero)
+    assert np.array_equal(x, y.astype(np.float32))
+    assert np.array_equal(bits, oracle.bitpack_i32(y))                   # sign(y) itself
+    x, bits = oracle.bn_sign_pack(y, -one, zero)
+    # -1 * 0 = -0.0, but -0.0 + (+0.0 shift) = +0.0 under round-to-nearest: y = 0 packs as +1
+    assert np.array_equal(bits, oracle.bitpack_i32(-y))
+    assert not np.signbit(x[y == 0]).any()
+    x, bits = oracle.bn_sign_pack(y, zero, one * 3, r=-4 * np.ones(y.shape, np.float32))
+    assert np.all(x == -1.0) and np.array_equal(bits, oracle.bitpack(x))
