@@ -95,6 +95,25 @@ int dabnn_nhwc_to_nc1hwc2(const uint64_t *in, uint64_t *out, int N, int H, int W
 int dabnn_nc1hwc2_to_nhwc(const uint64_t *in, uint64_t *out, int N, int H, int W, int Cw, void *stream);
 
 /*
+ * Fused batch-norm + shortcut + sign + bit-pack: the layer that sits between two binary
+ * convolutions.  Sec. 2.1.1 (last sentence) names the fused BN-binarization layer; the blocks of
+ * Bi-Real Net 18, the network of Sec. 2.3, add a real-valued shortcut before the next sign.  In
+ * IEEE single precision, every operation rounded separately (no fused multiply-add):
+ *
+ *   z[p,c] = ((scale[c] * (float)y[p,c]) + shift[c]) + r[p,c]          (r term absent if r is NULL)
+ *   bit    = IEEE sign bit of z            (the DABNN_SIGN_BIT rule; z = -0.0 packs as -1)
+ *
+ *   y     : i32 [n_pixels][C]  device   the output of dabnn_bconv2d
+ *   scale, shift : f32 [C]     device   folded batch-norm (gamma/sqrt(var+eps), beta - mean*scale)
+ *   r     : f32 [n_pixels][C]  device or NULL   the shortcut
+ *   x_out : f32 [n_pixels][C]  device or NULL   receives z (the next block's shortcut); may equal r
+ *   bits  : u64 [n_pixels][ceil(C/64)]  device, tail bits 0
+ * One HBM-bound pass: 4 (+4 +4) + 1/8 bytes per element instead of a float pass plus a bit-pack.
+ */
+int dabnn_bn_sign_pack(const int32_t *y, const float *scale, const float *shift, const float *r,
+                       float *x_out, uint64_t *bits, int64_t n_pixels, int C, void *stream);
+
+/*
  * Ahead-of-time packing of binary-convolution weights (Sec. 3), same bit rule as above.
  *   w   : fp32 [Cout][kh][kw][Cin], any values (only the sign is used), read only
  *   out : u64  [Cout][kh][kw][ceil(Cin/64)]   -- the canonical packed weight layout

@@ -44,6 +44,7 @@ def load():
     lib.dabnn_bitpack_i32.argtypes, lib.dabnn_bitpack_i32.restype = [vp, vp, i64, i32, vp], i32
     for f in (lib.dabnn_nhwc_to_nc1hwc2, lib.dabnn_nc1hwc2_to_nhwc):
         f.argtypes, f.restype = [vp, vp] + [i32] * 4 + [vp], i32
+    lib.dabnn_bn_sign_pack.argtypes, lib.dabnn_bn_sign_pack.restype = [vp] * 6 + [i64, i32, vp], i32
     lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
     lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
@@ -60,7 +61,7 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
            "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
            "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
-           "dabnn_nc1hwc2_to_nhwc"]
+           "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack"]
 
 
 def status_string(status):
@@ -212,6 +213,25 @@ def nc1hwc2_to_nhwc(g, Cw):
     _check(load().dabnn_nc1hwc2_to_nhwc(_dev(g, torch.int64, "g"), _dev(out, torch.int64, "out"), N, H, W,
                                         Cw, _stream()), "dabnn_nc1hwc2_to_nhwc")
     return out
+
+
+def bn_sign_pack(y, scale, shift, r=None, x_out=None, want_x=True, out=None):
+    """Fused BN + shortcut + sign + pack: y int32 [..., C], scale/shift float32 [C], r float32 like y
+    or None -> (z float32 like y or None, bits int64 [..., ceil(C/64)])."""
+    C = y.shape[-1]
+    n_pixels = y.numel() // C if C else 0
+    if x_out is None and want_x:
+        x_out = torch.empty(y.shape, dtype=torch.float32, device=y.device)
+    if out is None:
+        out = torch.empty(tuple(y.shape[:-1]) + ((C + 63) // 64,), dtype=torch.int64, device=y.device)
+    null = ctypes.c_void_p(0)
+    _check(load().dabnn_bn_sign_pack(_dev(y, torch.int32, "y"), _dev(scale, torch.float32, "scale"),
+                                     _dev(shift, torch.float32, "shift"),
+                                     _dev(r, torch.float32, "r") if r is not None else null,
+                                     _dev(x_out, torch.float32, "x_out") if x_out is not None else null,
+                                     _dev(out, torch.int64, "out"), n_pixels, C, _stream()),
+           "dabnn_bn_sign_pack")
+    return x_out, out
 
 
 def expand_int8(bits, C, out=None):

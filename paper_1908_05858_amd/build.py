@@ -12,6 +12,11 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# bitpack.hip holds the one kernel with float arithmetic (the fused BN + shortcut + sign layer),
+# whose operations must round separately: no contraction into fused multiply-adds in that file.
+EXTRA_FLAGS = {"bitpack.hip": ["-ffp-contract=off"]}
+
+
 def build_library(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
@@ -21,7 +26,7 @@ def build_library(verbose=False):
     for src in SOURCES:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd)))

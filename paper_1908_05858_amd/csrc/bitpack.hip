@@ -82,6 +82,87 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_kernel(
         out[g0 + lane] = make_uint2(lo, hi);
 }
 
+// Fused batch-norm + shortcut + sign + bit-pack between two binary convolutions (Sec. 2.1.1 names
+// the fused BN-binarization layer; Sec. 2.3's Bi-Real blocks add a real-valued shortcut first):
+//   z = ((scale[c] * float(y)) + shift[c]) + r,  every operation rounded separately (no FMA),
+// z optionally written out, its sign bits packed exactly as in bitpack_kernel: lane i handles
+// channel 64*j + i, so y, r and z move as coalesced 256-byte runs and one ballot is one word.
+// Bound by HBM: 4 (y) + 4 (r) + 4 (z) + 1/8 bytes per element.
+template <bool HAS_R, bool HAS_X, bool FLAT>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void bn_sign_pack_kernel(
+    const int32_t* __restrict__ y, const float* __restrict__ scale, const float* __restrict__ shift,
+    const float* __restrict__ r, float* __restrict__ x_out, uint2* __restrict__ out,
+    int64_t n_words, int C, int Cw)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t g0 =
+        (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block) * kWordsPerWave;
+    if (g0 >= n_words)
+        return;
+    // z for one element; the multiply and the adds must round separately: this file is compiled
+    // with -ffp-contract=off, so no v_fma_f32 / v_fmac_f32 is formed here
+    auto bn = [&](int c, int yv, float rv) {
+        float z = __fmul_rn(scale[c], static_cast<float>(yv));
+        z = __fadd_rn(z, shift[c]);
+        if (HAS_R)
+            z = __fadd_rn(z, rv);
+        return z;
+    };
+    uint32_t lo = 0, hi = 0;
+    if (FLAT && g0 + kWordsPerWave <= n_words) {
+        // C is a multiple of 64: word g covers the 64 consecutive elements from 64*g, and only
+        // the word's position within its pixel (wave-uniform) decides the channels
+        const int64_t e0 = g0 * 64 + lane;
+        int yv[kWordsPerWave];
+        float rv[kWordsPerWave];
+#pragma unroll
+        for (int k = 0; k < kWordsPerWave; ++k) {
+            yv[k] = __builtin_nontemporal_load(y + e0 + k * 64);
+            rv[k] = HAS_R ? __builtin_nontemporal_load(r + e0 + k * 64) : 0.0f;
+        }
+        int j = static_cast<int>(g0 % Cw);
+        static_for<0, kWordsPerWave>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            const float z = bn(64 * j + lane, yv[k], rv[k]);
+            if (HAS_X)
+                __builtin_nontemporal_store(z, x_out + e0 + k * 64);
+            const uint64_t word = __builtin_amdgcn_ballot_w64(static_cast<int32_t>(__float_as_uint(z)) < 0);
+            if (lane == k) {
+                lo = static_cast<uint32_t>(word);
+                hi = static_cast<uint32_t>(word >> 32);
+            }
+            j = (j + 1 == Cw) ? 0 : j + 1;
+        });
+    } else {
+        int64_t p = g0 / Cw;
+        int j = static_cast<int>(g0 - p * Cw);
+        static_for<0, kWordsPerWave>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            const int c = 64 * j + lane;
+            bool neg = false;  // a missing channel packs as bit 0
+            if (g0 + k < n_words && c < C) {
+                const int64_t e = p * C + c;
+                const float z = bn(c, y[e], HAS_R ? r[e] : 0.0f);
+                if (HAS_X)
+                    x_out[e] = z;
+                neg = static_cast<int32_t>(__float_as_uint(z)) < 0;
+            }
+            const uint64_t word = __builtin_amdgcn_ballot_w64(neg);
+            if (lane == k) {
+                lo = static_cast<uint32_t>(word);
+                hi = static_cast<uint32_t>(word >> 32);
+            }
+            if (++j == Cw) {
+                j = 0;
+                ++p;
+            }
+        });
+    }
+    if (lane < kWordsPerWave && g0 + lane < n_words)
+        out[g0 + lane] = make_uint2(lo, hi);
+}
+
 // NHWC words -> NC1HWC2 with C2 = 128 bits (Sec. 2.1.2): one thread per 16-byte group of the
 // output, so stores are fully coalesced; reads are two adjacent words of a pixel.
 __global__ __launch_bounds__(256) void nc1hwc2_kernel(const uint64_t* __restrict__ in,
@@ -121,6 +202,42 @@ hipError_t launch_nc1hwc2(const uint64_t* in, uint64_t* out, int N, int H, int W
         return hipErrorInvalidValue;
     nc1hwc2_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream>>>(
         in, reinterpret_cast<uint2*>(out), total, H * W, Cw, C1, to_grouped);
+    return hipGetLastError();
+}
+
+hipError_t launch_bn_sign_pack(const int32_t* y, const float* scale, const float* shift,
+                               const float* r, float* x_out, uint64_t* bits, int64_t n_rows, int C,
+                               hipStream_t stream)
+{
+    const int64_t Cw = (static_cast<int64_t>(C) + 63) / 64;
+    const int64_t n_words = n_rows * Cw;
+    if (n_words == 0)
+        return hipSuccess;
+    const int64_t per_block = static_cast<int64_t>(kWordsPerWave) * kWavesPerBlock;
+    const int64_t blocks = (n_words + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL)
+        return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(64 * kWavesPerBlock);
+    uint2* o = reinterpret_cast<uint2*>(bits);
+    const int cw = static_cast<int>(Cw);
+#define DABNN_LAUNCH(HR, HX)                                                                       \
+    do {                                                                                           \
+        if (C % 64 == 0)                                                                           \
+            bn_sign_pack_kernel<HR, HX, true><<<grid, block, 0, stream>>>(y, scale, shift, r, x_out, \
+                                                                          o, n_words, C, cw);      \
+        else                                                                                       \
+            bn_sign_pack_kernel<HR, HX, false><<<grid, block, 0, stream>>>(y, scale, shift, r,      \
+                                                                           x_out, o, n_words, C, cw); \
+    } while (0)
+    if (r && x_out)
+        DABNN_LAUNCH(true, true);
+    else if (r)
+        DABNN_LAUNCH(true, false);
+    else if (x_out)
+        DABNN_LAUNCH(false, true);
+    else
+        DABNN_LAUNCH(false, false);
+#undef DABNN_LAUNCH
     return hipGetLastError();
 }
 

@@ -132,6 +132,23 @@ int dabnn_nc1hwc2_to_nhwc(const uint64_t* in, uint64_t* out, int N, int H, int W
     return layout_call(in, out, N, H, W, Cw, false, stream);
 }
 
+int dabnn_bn_sign_pack(const int32_t* y, const float* scale, const float* shift, const float* r,
+                       float* x_out, uint64_t* bits, int64_t n_pixels, int C, void* stream)
+{
+    if (n_pixels < 0 || C <= 0 || n_pixels > (1LL << 40) / C)
+        return DABNN_ERR_SHAPE;
+    if (n_pixels == 0)
+        return DABNN_OK;
+    if (!y || !scale || !shift || !bits)
+        return DABNN_ERR_NULL;
+    if (!aligned(y, 4) || !aligned(scale, 4) || !aligned(shift, 4) || !aligned(r, 4) ||
+        !aligned(x_out, 4) || !aligned(bits, 8))
+        return DABNN_ERR_ALIGN;
+    const hipError_t e = dabnn::launch_bn_sign_pack(y, scale, shift, r, x_out, bits, n_pixels, C,
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
 int dabnn_pack_weights(const float* w, uint64_t* out, int Cout, int kh, int kw, int Cin,
                        int sign_mode, void* stream)
 {

@@ -16,6 +16,12 @@ struct ConvShape {
 hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, int sign_mode,
                           hipStream_t stream);
 
+// Fused BN + shortcut + sign + pack (Sec. 2.1.1 / 2.3): z = ((scale*y) + shift) + r in fp32 without
+// FMA, z -> x_out (optional), sign bits of z -> bits.  r and x_out may be null.
+hipError_t launch_bn_sign_pack(const int32_t* y, const float* scale, const float* shift,
+                               const float* r, float* x_out, uint64_t* bits, int64_t n_rows, int C,
+                               hipStream_t stream);
+
 // Packed NHWC [N][H][W][Cw] <-> NC1HWC2 [N][ceil(Cw/2)][H][W][2] (Sec. 2.1.2, C2 = 128 bits).
 hipError_t launch_nc1hwc2(const uint64_t* in, uint64_t* out, int N, int H, int W, int Cw,
                           bool to_grouped, hipStream_t stream);

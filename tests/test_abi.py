@@ -183,3 +183,13 @@ def test_layout_and_int32_pack_bad_arguments(lib):
         assert f(a, P(0), 1, 2, 2, 3, None) == 1
         assert f(a, o, 1, 0, 2, 3, None) == 2
         assert f(a, P(0x20004), 1, 2, 2, 3, None) == 3
+
+
+def test_bn_sign_pack_bad_arguments(lib):
+    P = ctypes.c_void_p
+    y, sc, sh, r, x, b = P(0x10000), P(0x20000), P(0x30000), P(0x40000), P(0x50000), P(0x60000)
+    assert lib.dabnn_bn_sign_pack(y, sc, P(0), r, x, b, 4, 64, None) == 1
+    assert lib.dabnn_bn_sign_pack(y, sc, sh, P(0), P(0), P(0), 4, 64, None) == 1   # bits is required
+    assert lib.dabnn_bn_sign_pack(y, sc, sh, r, x, b, -1, 64, None) == 2
+    assert lib.dabnn_bn_sign_pack(y, sc, sh, P(0x40002), x, b, 4, 64, None) == 3
+    assert lib.dabnn_bn_sign_pack(P(0), P(0), P(0), P(0), P(0), P(0), 0, 64, None) == 0

@@ -100,6 +100,42 @@ def test_nc1hwc2_round_trip(dabnn, oracle, shape):
     assert torch.equal(back, a_gpu)
 
 
+@pytest.mark.parametrize("C", [1, 64, 80, 128, 200, 512])
+@pytest.mark.parametrize("with_r,with_x", [(False, False), (True, True), (True, False), (False, True)])
+def test_bn_sign_pack(dabnn, oracle, C, with_r, with_x):
+    rng = np.random.default_rng(600 + C)
+    y = rng.integers(-1152, 1153, size=(5, 41, C)).astype(np.int32)
+    scale = rng.uniform(-0.1, 0.1, C).astype(np.float32)
+    scale[::6] = 0.0
+    shift = rng.normal(0, 1, C).astype(np.float32)
+    r = rng.normal(0, 2, y.shape).astype(np.float32) if with_r else None
+    x, bits = dabnn.bn_sign_pack(gpu(y), gpu(scale), gpu(shift), gpu(r) if with_r else None, want_x=with_x)
+    want_x, want_bits = oracle.bn_sign_pack(y, scale, shift, r)
+    assert np.array_equal(words(bits), want_bits)
+    if with_x:
+        assert np.array_equal(x.cpu().numpy().view(np.uint32), want_x.view(np.uint32))  # bit for bit
+    else:
+        assert x is None
+
+
+def test_bireal_block_chain(dabnn, oracle):
+    """Two Bi-Real-style blocks: bits -> conv -> BN + shortcut + sign + pack -> conv, against the
+    oracle chain; the second conv consumes the fused layer's words directly."""
+    N, H, W, C = 2, 14, 14, 128
+    x0 = wl.activations((N, H, W, C), 6100)
+    w1, w2 = wl.weights((C, 3, 3, C), 6101), wl.weights((C, 3, 3, C), 6102)
+    gamma, beta = wl.affine(C, 6103)
+    scale = (gamma / np.sqrt(np.float32(9 * C))).astype(np.float32)
+    y1 = dabnn.bconv2d(dabnn.bitpack(gpu(x0)), dabnn.pack_weights(gpu(w1)), C, 1, 1)
+    x1, a1 = dabnn.bn_sign_pack(y1, gpu(scale), gpu(beta), gpu(x0))
+    y2 = dabnn.bconv2d(a1, dabnn.pack_weights(gpu(w2)), C, 1, 1)
+    oy1 = oracle.bconv2d(x0, w1, 1, 1)
+    ox1, oa1 = oracle.bn_sign_pack(oy1, scale, beta, x0)
+    assert np.array_equal(x1.cpu().numpy().view(np.uint32), ox1.view(np.uint32))
+    assert np.array_equal(words(a1), oa1)
+    assert np.array_equal(y2.cpu().numpy(), oracle.bconv2d(ox1, w2, 1, 1))
+
+
 def test_pack_weights(dabnn, oracle):
     for shape in [(64, 3, 3, 64), (128, 3, 3, 80), (5, 1, 1, 200), (7, 5, 5, 3), (512, 3, 3, 512)]:
         w = wl.weights(shape, 77 + shape[0], p_plus=0.3)
