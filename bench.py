@@ -184,6 +184,36 @@ def main():
         mfma_conv_ms = (time.perf_counter() - t5) * 1e3 / k_cmp
         del w8s, a8s
 
+    # The same body with its real data dependencies (Sec. 2.3's network): each convolution reads
+    # the bits the previous block produced, and dabnn_bn_sign_pack turns its int32 output, plus the
+    # real-valued shortcut, into the next block's bits and shortcut.  Where the shape changes
+    # (stride 2) a resident synthetic tensor stands in for the float downsampling shortcut.
+    chain_ms = None
+    if all(L.Cout % 64 == 0 for L in layers):
+        scales = [torch.full((L.Cout,), 1.0 / (L.K ** 0.5), dtype=torch.float32, device="cuda") for L in layers]
+        shifts = [torch.from_numpy(wl.affine(L.Cout, wl.seed_for(5, 200 + li))[1]).cuda() for li, L in enumerate(layers)]
+        zs = [torch.empty((N, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
+        bits_out = [torch.empty((N, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
+        down = {li: torch.randn((N, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
+                if li == 0 or L.stride != 1}
+
+        def chain_step():
+            a_in = acts[0]
+            for li, L in enumerate(layers):
+                binding.bconv2d(a_in, wps[li], L.Cin, L.stride, 1, out=ys[li])
+                r = down[li] if li in down else zs[li - 1]
+                binding.bn_sign_pack(ys[li], scales[li], shifts[li], r, x_out=zs[li], out=bits_out[li])
+                a_in = bits_out[li]
+        chain_step()
+        torch.cuda.synchronize()
+        k_chain = max(4, args.steps // 4)
+        t6 = time.perf_counter()
+        for k in range(k_chain):
+            chain_step()
+        torch.cuda.synchronize()
+        chain_ms = (time.perf_counter() - t6) * 1e3 / k_chain
+        del zs, bits_out, down
+
     # The largest bit-pack shape of the parity configs (benchmark configs[2]: 256x56x56x256,
     # 822 MB of fp32), far beyond the 256 MB Infinity Cache: the launch the HBM fraction of the
     # bit-pack kernel is claimed on.  One HIP-event pair per launch.
@@ -272,6 +302,14 @@ def main():
         },
         "per_layer": per_layer,
     }
+    if chain_ms is not None:
+        result["bireal_block_chain"] = {
+            "what": "16 dependent blocks: dabnn_bconv2d on the previous block's bits, then "
+                    "dabnn_bn_sign_pack (BN + real-valued shortcut + sign + bit-pack) producing the "
+                    "next block's bits and shortcut",
+            "ms_per_step": round(chain_ms, 4),
+            "GOPS": round(total_ops / (chain_ms * 1e-3) / 1e9, 1),
+        }
     if big is not None:
         result["roofline_bitpack"]["largest_launch"] = big
     if mfma_ms is not None:

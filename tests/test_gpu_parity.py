@@ -629,3 +629,52 @@ def test_hip_graph_replay_of_the_hot_path(dabnn, oracle):
         assert np.array_equal(y.cpu().numpy(), oracle.bconv2d(x, wf, 1, 1)), rep
         assert np.array_equal(y0.cpu().numpy(), oracle.bconv2d_zeropad(x, wf, 1, 1)), rep
         assert np.array_equal(words(bits), oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, 1, 1)), rep
+
+
+# -------------------------------------------------------------------- seeded random shapes
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < n:
+        k = int(rng.choice([1, 3, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 2, 3]))
+        pad = int(rng.integers(0, k))
+        H, W = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        Cin = int(rng.choice([int(rng.integers(1, 600)), 64, 128, 256, 512]))
+        Cout = int(rng.choice([int(rng.integers(1, 200)), 16, 64, 128, 192]))
+        shapes.append((int(rng.integers(1, 5)), H, W, Cin, Cout, k, stride, pad))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_shapes(48, 20191908), ids=lambda s: "-".join(map(str, s)))
+def test_random_shapes_every_entry_point(dabnn, oracle, shape):
+    """Seeded random shapes through every convolution entry point the shape is valid for."""
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("random", shape, flush=True)
+    seed = 9000 + sum(shape)
+    x = wl.activations((N, H, W, Cin), seed)
+    wf = wl.weights((Cout, k, k, Cin), seed + 1, p_plus=0.4)
+    a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+    want = oracle.bconv2d(x, wf, stride, pad)
+    for algo in (0, 1, 2, 3, 4):
+        try:
+            got = dabnn.bconv2d(a, wp, Cin, stride, pad, algo=algo)
+        except dabnn.DabnnError as e:
+            assert e.status == 4 and algo in (2, 3, 4)   # that family does not cover the shape
+            continue
+        assert np.array_equal(got.cpu().numpy(), want), algo
+    assert np.array_equal(dabnn.bconv2d_zeropad(a, wp, Cin, stride, pad).cpu().numpy(),
+                          oracle.bconv2d_zeropad(x, wf, stride, pad))
+    gamma, beta, mean, var = _bn_params(Cout, seed + 2)
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, k * k * Cin)
+    assert np.array_equal(words(dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, stride, pad)),
+                          oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, stride, pad))
+    Cw = (Cin + 63) // 64
+    g = dabnn.bgemm(dabnn.im2col(a, Cin, k, k, stride, pad), wp.reshape(Cout, k * k * Cw), k * k * Cin)
+    assert np.array_equal(g.cpu().numpy().reshape(want.shape), want)
+    if Cin % 64 == 0 and Cout % 64 == 0:
+        y8 = dabnn.bconv2d_int8(dabnn.expand_int8(a, Cin), dabnn.expand_int8(wp, Cin), stride, pad)
+        assert np.array_equal(y8.cpu().numpy(), want)
