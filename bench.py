@@ -197,21 +197,27 @@ def main():
         down = {li: torch.randn((N, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
                 if li == 0 or L.stride != 1}
 
-        def chain_step():
+        def chain_step(fused):
             a_in = acts[0]
             for li, L in enumerate(layers):
-                binding.bconv2d(a_in, wps[li], L.Cin, L.stride, 1, out=ys[li])
                 r = down[li] if li in down else zs[li - 1]
-                binding.bn_sign_pack(ys[li], scales[li], shifts[li], r, x_out=zs[li], out=bits_out[li])
+                if fused:
+                    binding.bconv2d_bn_residual(a_in, wps[li], scales[li], shifts[li], r, L.Cin, L.stride, 1,
+                                                x_out=zs[li], out=bits_out[li])
+                else:
+                    binding.bconv2d(a_in, wps[li], L.Cin, L.stride, 1, out=ys[li])
+                    binding.bn_sign_pack(ys[li], scales[li], shifts[li], r, x_out=zs[li], out=bits_out[li])
                 a_in = bits_out[li]
-        chain_step()
-        torch.cuda.synchronize()
         k_chain = max(4, args.steps // 4)
-        t6 = time.perf_counter()
-        for k in range(k_chain):
-            chain_step()
-        torch.cuda.synchronize()
-        chain_ms = (time.perf_counter() - t6) * 1e3 / k_chain
+        chain_ms = []
+        for fused in (False, True):
+            chain_step(fused)
+            torch.cuda.synchronize()
+            t6 = time.perf_counter()
+            for k in range(k_chain):
+                chain_step(fused)
+            torch.cuda.synchronize()
+            chain_ms.append((time.perf_counter() - t6) * 1e3 / k_chain)
         del zs, bits_out, down
 
     # The largest bit-pack shape of the parity configs (benchmark configs[2]: 256x56x56x256,
@@ -304,11 +310,14 @@ def main():
     }
     if chain_ms is not None:
         result["bireal_block_chain"] = {
-            "what": "16 dependent blocks: dabnn_bconv2d on the previous block's bits, then "
-                    "dabnn_bn_sign_pack (BN + real-valued shortcut + sign + bit-pack) producing the "
-                    "next block's bits and shortcut",
-            "ms_per_step": round(chain_ms, 4),
-            "GOPS": round(total_ops / (chain_ms * 1e-3) / 1e9, 1),
+            "what": "16 dependent blocks: binary conv on the previous block's bits, then BN + real-valued "
+                    "shortcut + sign + bit-pack producing the next block's bits and shortcut; as two "
+                    "calls per block (dabnn_bconv2d, dabnn_bn_sign_pack) and as one "
+                    "(dabnn_bconv2d_bn_residual)",
+            "two_calls_per_block_ms_per_step": round(chain_ms[0], 4),
+            "two_calls_per_block_GOPS": round(total_ops / (chain_ms[0] * 1e-3) / 1e9, 1),
+            "one_call_per_block_ms_per_step": round(chain_ms[1], 4),   # dabnn_bconv2d_bn_residual
+            "one_call_per_block_GOPS": round(total_ops / (chain_ms[1] * 1e-3) / 1e9, 1),
         }
     if big is not None:
         result["roofline_bitpack"]["largest_launch"] = big

@@ -114,6 +114,24 @@ int dabnn_bn_sign_pack(const int32_t *y, const float *scale, const float *shift,
                        float *x_out, uint64_t *bits, int64_t n_pixels, int C, void *stream);
 
 /*
+ * dabnn_bconv2d followed by dabnn_bn_sign_pack in one call, without the int32 feature map: a whole
+ * Bi-Real-style block step (Sec. 2.3's network; Sec. 2.1.1's fused BN-binarization), bits in ->
+ * next bits and next shortcut out.  Results are exactly those of the two calls in sequence.
+ *   a, w         : as for dabnn_bconv2d
+ *   scale, shift : f32 [Cout]            device
+ *   r            : f32 [N][Ho][Wo][Cout] device or NULL (no shortcut)
+ *   x_out        : f32 [N][Ho][Wo][Cout] device, required (it doubles as the staging buffer of the
+ *                  int32 result for shapes the fused kernel does not cover); must not alias r
+ *   bits         : u64 [N][Ho][Wo][ceil(Cout/64)] device, tail bits 0
+ * The fused kernel runs 3x3 kernels, stride 1 or 2, ceil(Cin/64) in {1,2,4,8}, Cout % 64 == 0,
+ * a shortcut, and scale, shift, r, x_out 16-byte aligned; every other valid case runs as the two kernels in sequence.
+ */
+int dabnn_bconv2d_bn_residual(const uint64_t *a, const uint64_t *w, const float *scale,
+                              const float *shift, const float *r, float *x_out, uint64_t *bits,
+                              int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,
+                              int pad, void *stream);
+
+/*
  * Ahead-of-time packing of binary-convolution weights (Sec. 3), same bit rule as above.
  *   w   : fp32 [Cout][kh][kw][Cin], any values (only the sign is used), read only
  *   out : u64  [Cout][kh][kw][ceil(Cin/64)]   -- the canonical packed weight layout

@@ -45,6 +45,8 @@ def load():
     for f in (lib.dabnn_nhwc_to_nc1hwc2, lib.dabnn_nc1hwc2_to_nhwc):
         f.argtypes, f.restype = [vp, vp] + [i32] * 4 + [vp], i32
     lib.dabnn_bn_sign_pack.argtypes, lib.dabnn_bn_sign_pack.restype = [vp] * 6 + [i64, i32, vp], i32
+    lib.dabnn_bconv2d_bn_residual.argtypes = [vp] * 7 + [i32] * 9 + [vp]
+    lib.dabnn_bconv2d_bn_residual.restype = i32
     lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
     lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
@@ -61,7 +63,7 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
            "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
            "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
-           "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack"]
+           "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack", "dabnn_bconv2d_bn_residual"]
 
 
 def status_string(status):
@@ -231,6 +233,29 @@ def bn_sign_pack(y, scale, shift, r=None, x_out=None, want_x=True, out=None):
                                      _dev(x_out, torch.float32, "x_out") if x_out is not None else null,
                                      _dev(out, torch.int64, "out"), n_pixels, C, _stream()),
            "dabnn_bn_sign_pack")
+    return x_out, out
+
+
+def bconv2d_bn_residual(a, w, scale, shift, r, Cin, stride=1, pad=0, x_out=None, out=None):
+    """Conv + BN + shortcut + sign + pack in one call: packed a, w -> (z float32 [N,Ho,Wo,Cout],
+    bits int64 [N,Ho,Wo,ceil(Cout/64)]).  r may be None."""
+    N, H, W, Cw = a.shape
+    Cout, kh, kw, Cw2 = w.shape
+    if Cw != Cw2 or Cw != (Cin + 63) // 64:
+        raise ValueError("packed word counts do not match Cin")
+    Ho, Wo = conv_out_dim(H, kh, stride, pad), conv_out_dim(W, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_bn_residual")
+    if x_out is None:
+        x_out = torch.empty((N, Ho, Wo, Cout), dtype=torch.float32, device=a.device)
+    if out is None:
+        out = torch.empty((N, Ho, Wo, (Cout + 63) // 64), dtype=torch.int64, device=a.device)
+    _check(load().dabnn_bconv2d_bn_residual(
+        _dev(a, torch.int64, "a"), _dev(w, torch.int64, "w"), _dev(scale, torch.float32, "scale"),
+        _dev(shift, torch.float32, "shift"),
+        _dev(r, torch.float32, "r") if r is not None else ctypes.c_void_p(0),
+        _dev(x_out, torch.float32, "x_out"), _dev(out, torch.int64, "out"), N, H, W, Cin, Cout, kh, kw,
+        stride, pad, _stream()), "dabnn_bconv2d_bn_residual")
     return x_out, out
 
 

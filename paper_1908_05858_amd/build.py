@@ -15,6 +15,8 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "
 # bitpack.hip holds the one kernel with float arithmetic (the fused BN + shortcut + sign layer),
 # whose operations must round separately: no contraction into fused multiply-adds in that file.
 EXTRA_FLAGS = {"bitpack.hip": ["-ffp-contract=off"]}
+# ... and so does the BN + shortcut epilogue of the activation-stationary convolution kernels.
+EXTRA_FLAGS.update({f"bconv_areg_cw{cw}_s{st}.hip": ["-ffp-contract=off"] for cw in (1, 2, 4, 8) for st in (1, 2)})
 
 
 def build_library(verbose=False):

@@ -9,7 +9,11 @@ namespace dabnn {
                                          const ConvShape& s, hipStream_t stream);                 \
     hipError_t launch_bits_cw##CW##_s##S(const uint32_t* a, const uint32_t* w, uint64_t* out,      \
                                          const ConvShape& s, hipStream_t stream,                  \
-                                         const int32_t* thr, const uint2* flip);
+                                         const int32_t* thr, const uint2* flip);                  \
+    hipError_t launch_res_cw##CW##_s##S(const uint32_t* a, const uint32_t* w, const ConvShape& s,  \
+                                        hipStream_t stream, const float* scale,                   \
+                                        const float* shift, const float* r, float* x_out,         \
+                                        uint64_t* bits);
 DABNN_DECLARE(1, 1) DABNN_DECLARE(1, 2) DABNN_DECLARE(2, 1) DABNN_DECLARE(2, 2)
 DABNN_DECLARE(4, 1) DABNN_DECLARE(4, 2) DABNN_DECLARE(8, 1) DABNN_DECLARE(8, 2)
 #undef DABNN_DECLARE
@@ -52,6 +56,35 @@ hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const 
             return s.stride == 1 ? launch_bits_cw8_s1(a32, w32, out, s, stream, thr, f2)
                                  : launch_bits_cw8_s2(a32, w32, out, s, stream, thr, f2);
     }
+}
+
+bool bconv_bn_residual_areg_supports(const ConvShape& s, const void* scale, const void* shift,
+                                     const void* r, const void* x_out)
+{
+    // 16-byte loads of scale, shift and r, 16-byte stores of x_out, whole output words
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(shift) |
+                           reinterpret_cast<uintptr_t>(r) | reinterpret_cast<uintptr_t>(x_out);
+    return bconv_bnsign_areg_supports(s) && r != nullptr && (bits & 15) == 0;
+}
+
+hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, const float* scale,
+                                         const float* shift, const float* r, float* x_out,
+                                         uint64_t* bits, const ConvShape& s, hipStream_t stream)
+{
+    if (!bconv_bn_residual_areg_supports(s, scale, shift, r, x_out))
+        return hipErrorNotSupported;
+    const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
+    const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
+#define DABNN_CASE(CW)                                                                             \
+    return s.stride == 1 ? launch_res_cw##CW##_s1(a32, w32, s, stream, scale, shift, r, x_out, bits) \
+                         : launch_res_cw##CW##_s2(a32, w32, s, stream, scale, shift, r, x_out, bits)
+    switch (s.Cw) {
+        case 1: DABNN_CASE(1);
+        case 2: DABNN_CASE(2);
+        case 4: DABNN_CASE(4);
+        default: DABNN_CASE(8);
+    }
+#undef DABNN_CASE
 }
 
 bool bconv_areg_supports(const ConvShape& s, const void* y)

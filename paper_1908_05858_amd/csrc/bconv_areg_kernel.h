@@ -123,13 +123,26 @@ __device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
 //   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
 //   an output word).
 constexpr int kBits = -1;
+constexpr int kRes = -3;  // fused BN + shortcut epilogue: float z and its packed sign bits
+
+// Extra operands of the kRes mode.  It is the FIRST kernel parameter, so it sits at offset 0 of
+// the kernel-argument segment and the epilogue can fetch its fields from there with scalar loads
+// when it needs them, instead of holding ten more SGPRs through the main loop.
+struct ResArgs {
+    const float* scale;   // [Cout]
+    const float* shift;   // [Cout]
+    const float* r;       // [N][Ho][Wo][Cout], not null
+    float* x_out;         // [N][Ho][Wo][Cout]
+    uint16_t* bits16;     // the packed output viewed as [N*Ho*Wo][Cout/16] half-words
+};
 constexpr int kTailTR = 16;  // the store mode whose uneven remainder is split into small pieces
 constexpr int kDC = 6;
 template <int CW, int TR>
 struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
-    static constexpr int CG = TR > 0 ? TR : (TR == kBits ? 16 : (CW == 1 ? 8 : 4));
+    static constexpr int CG =
+        TR > 0 ? TR : ((TR == kBits || TR == kRes) ? 16 : (CW == 1 ? 8 : 4));
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
@@ -168,13 +181,14 @@ __device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int 
 
 template <int CW, int S, int TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
+    ResArgs /* read through the kernel-argument segment, see ResArgs */,
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
     int n_ranges, int base_groups, int rem_groups, int tail_first, int tail_base, int tail_rem,
     const int32_t* __restrict__ thr, const uint2* __restrict__ flip)
 {
     // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
-    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : 4];
+    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : (TR == kRes ? 4 * 64 * 16 : 4)];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -271,6 +285,23 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             }
         }
 
+        // kRes: the shortcut values this lane will need in the epilogue (pixel 16k + lane/4,
+        // channels 4*(lane%4)..+3 of this group), requested now so that they arrive during the
+        // group's arithmetic.
+        float4 r_pre[TRX == kRes ? 4 : 1];
+        if constexpr (TRX == kRes) {
+            const ResArgs* ka = (const ResArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+            const float* rp = ka->r;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int P = 16 * k + (lane >> 2);
+                r_pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (tile * 64 + P < total_pix)
+                    r_pre[k] = *reinterpret_cast<const float4*>(
+                        rp + static_cast<size_t>(tile * 64 + P) * Cout + cgi * 16 + 4 * (lane & 3));
+            }
+        }
+
         // Software pipeline: while unit u feeds the VALU, unit u+1 is in flight.
         static_for<0, G::UNITS>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
@@ -319,6 +350,73 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     reinterpret_cast<uint16_t*>(y)[2 * half_index + (odd ? 1 : 0)] =
                         static_cast<uint16_t>((rev >> 16) ^ fl16);
             }
+        } else if constexpr (TRX == kRes) {
+            // Fused BN + shortcut epilogue.  The 64 x 16 tile of y goes through the LDS transpose
+            // of the 16-channel store mode; afterwards lane (P, j) holds channels 4j..4j+3 of pixel
+            // P, reads the matching 16 bytes of the shortcut, forms
+            //   z = ((scale * float(y)) + shift) + r      (separately rounded: no FMA in this file)
+            // stores z, and contributes 4 sign bits; the four lanes of a pixel OR them together
+            // and one of them stores the group's 16 bits.
+            auto swz = [](int P) { return (P >> 1) & 3; };
+            int32_t* slice = tile_lds + wave * (64 * 16);
+            {
+                const int sw = swz(lane);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int4 o;
+                    o.x = finish_output(acc[4 * j + 0], K);
+                    o.y = finish_output(acc[4 * j + 1], K);
+                    o.z = finish_output(acc[4 * j + 2], K);
+                    o.w = finish_output(acc[4 * j + 3], K);
+                    *reinterpret_cast<int4*>(slice + lane * 16 + 4 * (j ^ sw)) = o;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // the extra operands, fetched now from the kernel-argument segment (offset 0)
+            const ResArgs* ka = (const ResArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+            const float* scale = ka->scale;
+            const float* shift = ka->shift;
+            float* xo = ka->x_out;
+            uint16_t* bits16 = ka->bits16;
+            const int j = lane & 3;
+            const int c0 = cgi * 16 + 4 * j;
+            const float4 sc = *reinterpret_cast<const float4*>(scale + c0);
+            const float4 sh = *reinterpret_cast<const float4*>(shift + c0);
+            const uint32_t row0 = static_cast<uint32_t>(tile) * 64u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int P = 16 * k + (lane >> 2);
+                const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ swz(P)));
+                const bool ok = static_cast<int>(row0) + P < total_pix;
+                const size_t e = static_cast<size_t>(row0 + P) * Cout + c0;
+                const float4 rr = r_pre[k];
+                float4 z;
+                z.x = __fadd_rn(__fmul_rn(sc.x, static_cast<float>(o.x)), sh.x);
+                z.y = __fadd_rn(__fmul_rn(sc.y, static_cast<float>(o.y)), sh.y);
+                z.z = __fadd_rn(__fmul_rn(sc.z, static_cast<float>(o.z)), sh.z);
+                z.w = __fadd_rn(__fmul_rn(sc.w, static_cast<float>(o.w)), sh.w);
+                z.x = __fadd_rn(z.x, rr.x);
+                z.y = __fadd_rn(z.y, rr.y);
+                z.z = __fadd_rn(z.z, rr.z);
+                z.w = __fadd_rn(z.w, rr.w);
+                if (ok) {
+                    typedef float v4f __attribute__((ext_vector_type(4)));
+                    v4f zv = {z.x, z.y, z.z, z.w};
+                    __builtin_nontemporal_store(zv, reinterpret_cast<v4f*>(xo + e));
+                }
+                uint32_t nib = (__float_as_uint(z.x) >> 31) | ((__float_as_uint(z.y) >> 31) << 1) |
+                               ((__float_as_uint(z.z) >> 31) << 2) | ((__float_as_uint(z.w) >> 31) << 3);
+                nib <<= 4 * j;
+                // OR over the four lanes of the pixel (lanes 4q..4q+3): xor-1 then xor-2 partners
+                nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0xB1, 0xF, 0xF, true));
+                nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0x4E, 0xF, 0xF, true));
+                if (ok && j == 0)
+                    bits16[static_cast<size_t>(row0 + P) * (Cout >> 4) + cgi] = static_cast<uint16_t>(nib);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         } else if constexpr (TRX != 0) {
             // Row P of the wavefront's LDS slice holds pixel P's TRX channels as QPR 16-byte quads.
             // Quad j sits in column j ^ swz(P), which makes both the row-wise writes and the
@@ -413,7 +511,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
 template <int CW, int S, int TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream, const int32_t* thr = nullptr,
-                            const uint2* flip = nullptr)
+                            const uint2* flip = nullptr, const ResArgs& res = ResArgs{})
 {
     using G = AregGeom<CW, TR>;
     static_assert(G::UNITS % 2 == 0 && G::KD % kDC == 0, "pipeline geometry");
@@ -454,7 +552,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
         rem_groups = 0;
     }
     const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, res, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
                        s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
                        rem_groups, tail_first, tail_base, tail_rem, thr, flip);
     return hipGetLastError();
@@ -493,6 +591,14 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     {                                                                                             \
         return launch_areg_inst<CW, S, kBits>(a, w, reinterpret_cast<int32_t*>(out), s, stream,   \
                                               thr, flip);                                         \
+    }                                                                                             \
+    hipError_t launch_res_cw##CW##_s##S(const uint32_t* a, const uint32_t* w, const ConvShape& s,  \
+                                        hipStream_t stream, const float* scale,                   \
+                                        const float* shift, const float* r, float* x_out,         \
+                                        uint64_t* bits)                                           \
+    {                                                                                             \
+        const ResArgs res{scale, shift, r, x_out, reinterpret_cast<uint16_t*>(bits)};             \
+        return launch_areg_inst<CW, S, kRes>(a, w, nullptr, s, stream, nullptr, nullptr, res);    \
     }
 
 }  // namespace dabnn

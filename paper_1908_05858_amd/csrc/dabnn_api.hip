@@ -313,6 +313,38 @@ int dabnn_bconv2d_bnsign(const uint64_t* a, const uint64_t* w, const int32_t* th
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
+int dabnn_bconv2d_bn_residual(const uint64_t* a, const uint64_t* w, const float* scale,
+                              const float* shift, const float* r, float* x_out, uint64_t* bits,
+                              int N, int H, int W, int Cin, int Cout, int kh, int kw, int stride,
+                              int pad, void* stream)
+{
+    if (!a || !w || !scale || !shift || !x_out || !bits)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (!aligned(a, 8) || !aligned(w, 8) || !aligned(scale, 4) || !aligned(shift, 4) ||
+        !aligned(r, 4) || !aligned(x_out, 4) || !aligned(bits, 8))
+        return DABNN_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dabnn::bconv_bn_residual_areg_supports(s, scale, shift, r, x_out)) {
+        const hipError_t e =
+            dabnn::launch_bconv_bn_residual_areg(a, w, scale, shift, r, x_out, bits, s, st);
+        return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+    }
+    // Any other shape: the convolution writes its int32 result into x_out's storage (same size),
+    // and the layer kernel turns every element into z in place (each thread reads y[e] before it
+    // writes z[e]).
+    int32_t* y = reinterpret_cast<int32_t*>(x_out);
+    const int rc2 = dabnn_bconv2d(a, w, y, N, H, W, Cin, Cout, kh, kw, stride, pad, stream);
+    if (rc2 != DABNN_OK)
+        return rc2;
+    const hipError_t e = dabnn::launch_bn_sign_pack(y, scale, shift, r, x_out, bits,
+                                                    static_cast<int64_t>(N) * s.Ho * s.Wo, Cout, st);
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
 int dabnn_bn_thresholds(const float* gamma, const float* beta, const float* mean, const float* var,
                         float eps, int Cout, int K, int32_t* thr, uint64_t* flip)
 {

@@ -60,6 +60,12 @@ hipError_t launch_expand_pm1(const uint64_t* bits, int8_t* out, int64_t rows, in
 hipError_t launch_bconv_mfma_i8(const int8_t* a8, const int8_t* w8, int32_t* y, const ConvShape& s,
                                 hipStream_t stream);
 bool bconv_mfma_supports(const ConvShape& s);
+// Convolution with the BN + shortcut + sign + pack layer fused into its epilogue (no int32 tensor).
+hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, const float* scale,
+                                         const float* shift, const float* r, float* x_out,
+                                         uint64_t* bits, const ConvShape& s, hipStream_t stream);
+bool bconv_bn_residual_areg_supports(const ConvShape& s, const void* scale, const void* shift,
+                                     const void* r, const void* x_out);
 bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);

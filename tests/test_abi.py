@@ -193,3 +193,13 @@ def test_bn_sign_pack_bad_arguments(lib):
     assert lib.dabnn_bn_sign_pack(y, sc, sh, r, x, b, -1, 64, None) == 2
     assert lib.dabnn_bn_sign_pack(y, sc, sh, P(0x40002), x, b, 4, 64, None) == 3
     assert lib.dabnn_bn_sign_pack(P(0), P(0), P(0), P(0), P(0), P(0), 0, 64, None) == 0
+
+
+def test_bn_residual_bad_arguments(lib):
+    P = ctypes.c_void_p
+    a, w, sc, sh, r, x, b = (P(v) for v in (0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, 0x70000))
+    args = (1, 4, 4, 64, 64, 3, 3, 1, 1, None)
+    assert lib.dabnn_bconv2d_bn_residual(a, w, sc, sh, r, P(0), b, *args) == 1    # x_out is required
+    assert lib.dabnn_bconv2d_bn_residual(a, w, P(0), sh, r, x, b, *args) == 1
+    assert lib.dabnn_bconv2d_bn_residual(a, w, sc, sh, r, x, b, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2
+    assert lib.dabnn_bconv2d_bn_residual(a, w, sc, sh, P(0x50002), x, b, *args) == 3

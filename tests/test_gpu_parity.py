@@ -118,6 +118,69 @@ def test_bn_sign_pack(dabnn, oracle, C, with_r, with_x):
         assert x is None
 
 
+RESIDUAL_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
+    (1, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 1, 1), (2, 28, 28, 128, 256, 3, 2, 1),
+    (2, 9, 13, 256, 192, 3, 1, 1), (2, 7, 7, 512, 512, 3, 1, 1), (5, 57, 30, 64, 64, 3, 1, 1),
+    (1, 3, 3, 64, 64, 3, 1, 1), (3, 11, 10, 64, 128, 3, 2, 1),
+    # the two-kernel route: other kernel sizes, channel counts, strides
+    (2, 6, 6, 128, 64, 1, 1, 0), (1, 10, 17, 200, 33, 3, 2, 1), (1, 12, 12, 64, 16, 5, 1, 2),
+    (2, 13, 11, 80, 130, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("with_r", [True, False])
+@pytest.mark.parametrize("shape", RESIDUAL_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_bconv2d_bn_residual(dabnn, oracle, shape, with_r):
+    """One call against the oracle's convolution followed by the oracle's BN + shortcut + sign +
+    pack layer; z compared bit for bit."""
+    N, H, W, Cin, Cout, k, stride, pad = shape
+    print("residual", shape, with_r, flush=True)
+    seed = 7000 + sum(shape)
+    x = wl.activations((N, H, W, Cin), seed)
+    wf = wl.weights((Cout, k, k, Cin), seed + 1)
+    rng = np.random.default_rng(seed + 2)
+    scale = rng.uniform(-0.1, 0.1, Cout).astype(np.float32)
+    scale[::7] = 0.0
+    shift = rng.normal(0, 1, Cout).astype(np.float32)
+    oy = oracle.bconv2d(x, wf, stride, pad)
+    r = rng.normal(0, 2, oy.shape).astype(np.float32) if with_r else None
+    want_z, want_bits = oracle.bn_sign_pack(oy, scale, shift, r)
+    z, bits = dabnn.bconv2d_bn_residual(dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf)), gpu(scale),
+                                        gpu(shift), gpu(r) if with_r else None, Cin, stride, pad)
+    assert np.array_equal(z.cpu().numpy().view(np.uint32), want_z.view(np.uint32))
+    assert np.array_equal(words(bits), want_bits)
+
+
+@pytest.mark.parametrize("slots", [1, 5, 64])
+def test_bconv2d_bn_residual_work_split(dabnn, oracle, slots, monkeypatch):
+    monkeypatch.setenv("DABNN_AREG_SLOTS", str(slots))
+    test_bconv2d_bn_residual(dabnn, oracle, (2, 14, 14, 128, 128, 3, 1, 1), True)
+    test_bconv2d_bn_residual(dabnn, oracle, (3, 9, 7, 64, 192, 3, 2, 1), False)
+
+
+def test_bconv2d_bn_residual_full_batch_layer(dabnn, oracle):
+    """Batch 256 at a benchmark shape: sampled pixels (all channels) against the oracle chain, and
+    the whole result against the library's own two-call sequence."""
+    L = wl.BIREAL18_BODY[5]
+    N = wl.CFG5_BATCH
+    x = wl.activations((N, L.H, L.W, L.Cin), wl.seed_for(5, 105))
+    wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, 5))
+    rng = np.random.default_rng(55)
+    scale = rng.uniform(0.01, 0.05, L.Cout).astype(np.float32)
+    shift = rng.normal(0, 1, L.Cout).astype(np.float32)
+    r = rng.normal(0, 1, (N, L.Ho, L.Wo, L.Cout)).astype(np.float32)
+    a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+    rg, sg, hg = gpu(r), gpu(scale), gpu(shift)
+    z, bits = dabnn.bconv2d_bn_residual(a, wp, sg, hg, rg, L.Cin, L.stride, 1)
+    z2, bits2 = dabnn.bn_sign_pack(dabnn.bconv2d(a, wp, L.Cin, L.stride, 1), sg, hg, rg)
+    assert torch.equal(z.view(torch.int32), z2.view(torch.int32)) and torch.equal(bits, bits2)
+    for n in (0, N // 2, N - 1):
+        oy = oracle.bconv2d(x[n:n + 1], wf, L.stride, 1)
+        oz, ob = oracle.bn_sign_pack(oy, scale, shift, r[n:n + 1])
+        assert np.array_equal(z[n:n + 1].cpu().numpy().view(np.uint32), oz.view(np.uint32))
+        assert np.array_equal(words(bits[n:n + 1]), ob)
+
+
 def test_bireal_block_chain(dabnn, oracle):
     """Two Bi-Real-style blocks: bits -> conv -> BN + shortcut + sign + pack -> conv, against the
     oracle chain; the second conv consumes the fused layer's words directly."""
