@@ -123,7 +123,31 @@ __device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
 //   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
 //   an output word).
 constexpr int kBits = -1;
-constexpr int kRes = -3;  // fused BN + shortcut epilogue: float z and its packed sign bits
+constexpr int kRes = -3;    // fused BN + shortcut epilogue: float z and its packed sign bits
+constexpr int kRes32 = -4;  // the same with 32 channels per group (128-byte runs of r and z)
+constexpr bool is_res(int tr) { return tr == kRes || tr == kRes32; }
+
+// What the window load needs, and nothing else does: the second kernel parameter.  The window
+// is loaded once per 64-pixel tile, so these are fetched from the kernel-argument segment at that
+// point (scalar loads) instead of occupying a dozen SGPRs through the main loop.  Divisions by
+// Ho*Wo and Wo use multiply-shift constants prepared on the host.
+struct WindowArgs {
+    const uint32_t* a;
+    int H, W, Ho, Wo, pad;
+    uint32_t hw, hw_mul, hw_shift;  // Ho*Wo and its division constants
+    uint32_t wo_mul, wo_shift;      // division constants of Wo
+};
+
+// floor(n / d) for any 32-bit n, with mul = floor(2^32 * (2^L - d) / d) + 1 and shift = L - 1,
+// L = ceil(log2 d) (d = 1: mul = 0 would need a 33-bit step, so the host passes shift = 32,
+// which selects the identity).
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t shift)
+{
+    if (shift == 32)
+        return n;
+    const uint32_t t = __umulhi(mul, n);
+    return (t + ((n - t) >> 1)) >> shift;
+}
 
 // Extra operands of the kRes mode.  It is the FIRST kernel parameter, so it sits at offset 0 of
 // the kernel-argument segment and the epilogue can fetch its fields from there with scalar loads
@@ -142,7 +166,7 @@ struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
     static constexpr int CG =
-        TR > 0 ? TR : ((TR == kBits || TR == kRes) ? 16 : (CW == 1 ? 8 : 4));
+        TR > 0 ? TR : (TR == kRes32 ? 32 : ((TR == kBits || TR == kRes) ? 16 : (CW == 1 ? 8 : 4)));
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
@@ -182,13 +206,14 @@ __device__ __forceinline__ void areg_compute_unit(const uint32_t (&sb)[SB], int 
 template <int CW, int S, int TR>
 __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     ResArgs /* read through the kernel-argument segment, see ResArgs */,
-    const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
-    int H, int W, int Cout, int Ho, int Wo, int pad, int K, int total_pix, int groups_per_tile,
+    WindowArgs /* likewise, at offset sizeof(ResArgs) */,
+    const uint32_t* __restrict__ w, int32_t* __restrict__ y,
+    int Cout, int K, int total_pix, int groups_per_tile,
     int n_ranges, int base_groups, int rem_groups, int tail_first, int tail_base, int tail_rem,
     const int32_t* __restrict__ thr, const uint2* __restrict__ flip)
 {
     // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
-    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : (TR == kRes ? 4 * 64 * 16 : 4)];
+    __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : (is_res(TR) ? 4 * 64 * AregGeom<CW, TR>::CG : 4)];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -202,12 +227,19 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     // The 3x3xCw window under this lane's output pixel; taps outside the image become zero
     // words (every channel +1).
     auto load_window = [&](int t) {
+        // the window operands, fetched now from the kernel-argument segment
+        uint64_t wa_addr = reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()) + sizeof(ResArgs);
+        asm volatile("" : "+s"(wa_addr));  // re-read per tile: do not keep the fields in SGPRs
+        const auto* wa = reinterpret_cast<const WindowArgs __attribute__((address_space(4)))*>(wa_addr);
+        const uint32_t* a = wa->a;
+        const int H = wa->H, W = wa->W, pad = wa->pad;
+        const int Wo = wa->Wo;
         const int p = t * 64 + lane;
         pvalid = p < total_pix;
         const int pc = pvalid ? p : total_pix - 1;
-        const int n = pc / (Ho * Wo);
-        const int r = pc - n * (Ho * Wo);
-        const int ho = r / Wo;
+        const int n = static_cast<int>(fast_div(static_cast<uint32_t>(pc), wa->hw_mul, wa->hw_shift));
+        const int r = pc - n * static_cast<int>(wa->hw);
+        const int ho = static_cast<int>(fast_div(static_cast<uint32_t>(r), wa->wo_mul, wa->wo_shift));
         const int wo = r - ho * Wo;
         ybase = static_cast<uint32_t>(pc) * static_cast<uint32_t>(Cout);
         // Pixel index of the window's top-left tap; taps are addressed as a uniform base plus a
@@ -285,20 +317,21 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             }
         }
 
-        // kRes: the shortcut values this lane will need in the epilogue (pixel 16k + lane/4,
-        // channels 4*(lane%4)..+3 of this group), requested now so that they arrive during the
-        // group's arithmetic.
-        float4 r_pre[TRX == kRes ? 4 : 1];
-        if constexpr (TRX == kRes) {
+        // kRes: the shortcut values this lane will need in the epilogue (QPR lanes per pixel:
+        // pixel PPI*k + lane/QPR, channels 4*(lane%QPR)..+3 of this group), requested now so that
+        // they arrive during the group's arithmetic.
+        constexpr int RQPR = is_res(TRX) ? G::CG / 4 : 1;
+        float4 r_pre[RQPR];
+        if constexpr (is_res(TRX)) {
             const ResArgs* ka = (const ResArgs*)__builtin_amdgcn_kernarg_segment_ptr();
             const float* rp = ka->r;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int P = 16 * k + (lane >> 2);
+            for (int k = 0; k < RQPR; ++k) {
+                const int P = (64 / RQPR) * k + lane / RQPR;
                 r_pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (tile * 64 + P < total_pix)
                     r_pre[k] = *reinterpret_cast<const float4*>(
-                        rp + static_cast<size_t>(tile * 64 + P) * Cout + cgi * 16 + 4 * (lane & 3));
+                        rp + static_cast<size_t>(tile * 64 + P) * Cout + cgi * G::CG + 4 * (lane % RQPR));
             }
         }
 
@@ -350,25 +383,28 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                     reinterpret_cast<uint16_t*>(y)[2 * half_index + (odd ? 1 : 0)] =
                         static_cast<uint16_t>((rev >> 16) ^ fl16);
             }
-        } else if constexpr (TRX == kRes) {
-            // Fused BN + shortcut epilogue.  The 64 x 16 tile of y goes through the LDS transpose
-            // of the 16-channel store mode; afterwards lane (P, j) holds channels 4j..4j+3 of pixel
-            // P, reads the matching 16 bytes of the shortcut, forms
+        } else if constexpr (is_res(TRX)) {
+            // Fused BN + shortcut epilogue.  The 64 x CG tile of y goes through the LDS transpose
+            // of the transposed store modes (CG = 16 or 32); afterwards lane (P, j) holds channels
+            // 4j..4j+3 of pixel P, takes the matching 16 bytes of the shortcut, forms
             //   z = ((scale * float(y)) + shift) + r      (separately rounded: no FMA in this file)
-            // stores z, and contributes 4 sign bits; the four lanes of a pixel OR them together
-            // and one of them stores the group's 16 bits.
-            auto swz = [](int P) { return (P >> 1) & 3; };
-            int32_t* slice = tile_lds + wave * (64 * 16);
+            // stores z, and contributes 4 sign bits; the four lanes of a 16-channel quarter OR
+            // them together and one of them stores those 16 bits.
+            constexpr int CGR = G::CG;
+            constexpr int QPR = CGR / 4;   // lanes per pixel
+            constexpr int PPI = 64 / QPR;  // pixels per pass
+            auto swz = [](int P) { return (CGR == 16) ? ((P >> 1) & 3) : (P & 7); };
+            int32_t* slice = tile_lds + wave * (64 * CGR);
             {
                 const int sw = swz(lane);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < QPR; ++j) {
                     int4 o;
                     o.x = finish_output(acc[4 * j + 0], K);
                     o.y = finish_output(acc[4 * j + 1], K);
                     o.z = finish_output(acc[4 * j + 2], K);
                     o.w = finish_output(acc[4 * j + 3], K);
-                    *reinterpret_cast<int4*>(slice + lane * 16 + 4 * (j ^ sw)) = o;
+                    *reinterpret_cast<int4*>(slice + lane * CGR + 4 * (j ^ sw)) = o;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -380,15 +416,15 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
             const float* shift = ka->shift;
             float* xo = ka->x_out;
             uint16_t* bits16 = ka->bits16;
-            const int j = lane & 3;
-            const int c0 = cgi * 16 + 4 * j;
+            const int j = lane % QPR;
+            const int c0 = cgi * CGR + 4 * j;
             const float4 sc = *reinterpret_cast<const float4*>(scale + c0);
             const float4 sh = *reinterpret_cast<const float4*>(shift + c0);
             const uint32_t row0 = static_cast<uint32_t>(tile) * 64u;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int P = 16 * k + (lane >> 2);
-                const int4 o = *reinterpret_cast<const int4*>(slice + P * 16 + 4 * (j ^ swz(P)));
+            for (int k = 0; k < QPR; ++k) {
+                const int P = PPI * k + lane / QPR;
+                const int4 o = *reinterpret_cast<const int4*>(slice + P * CGR + 4 * (j ^ swz(P)));
                 const bool ok = static_cast<int>(row0) + P < total_pix;
                 const size_t e = static_cast<size_t>(row0 + P) * Cout + c0;
                 const float4 rr = r_pre[k];
@@ -408,12 +444,13 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                 }
                 uint32_t nib = (__float_as_uint(z.x) >> 31) | ((__float_as_uint(z.y) >> 31) << 1) |
                                ((__float_as_uint(z.z) >> 31) << 2) | ((__float_as_uint(z.w) >> 31) << 3);
-                nib <<= 4 * j;
-                // OR over the four lanes of the pixel (lanes 4q..4q+3): xor-1 then xor-2 partners
+                nib <<= 4 * (j & 3);
+                // OR over the four lanes of a quarter (lanes 4q..4q+3): xor-1 then xor-2 partners
                 nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0xB1, 0xF, 0xF, true));
                 nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0x4E, 0xF, 0xF, true));
-                if (ok && j == 0)
-                    bits16[static_cast<size_t>(row0 + P) * (Cout >> 4) + cgi] = static_cast<uint16_t>(nib);
+                if (ok && (j & 3) == 0)
+                    bits16[static_cast<size_t>(row0 + P) * (Cout >> 4) + cgi * (CGR / 16) + (j >> 2)] =
+                        static_cast<uint16_t>(nib);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -508,6 +545,21 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     }
 }
 
+// Constants of fast_div for the divisor d >= 1.
+inline void division_constants(uint32_t d, uint32_t& mul, uint32_t& shift)
+{
+    if (d == 1) {
+        mul = 0;
+        shift = 32;
+        return;
+    }
+    uint32_t L = 0;
+    while ((uint64_t{1} << L) < d)
+        ++L;  // L = ceil(log2 d) >= 1
+    mul = static_cast<uint32_t>(((uint64_t{1} << 32) * ((uint64_t{1} << L) - d)) / d + 1);
+    shift = L - 1;
+}
+
 template <int CW, int S, int TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream, const int32_t* thr = nullptr,
@@ -552,7 +604,11 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
         rem_groups = 0;
     }
     const dim3 grid(static_cast<unsigned>((n_ranges + 3) / 4)), block(256);
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, res, a, w, y, s.H, s.W, s.Cout, s.Ho, s.Wo, s.pad,
+    WindowArgs wa{a, s.H, s.W, s.Ho, s.Wo, s.pad, 0, 0, 0, 0, 0};
+    wa.hw = static_cast<uint32_t>(s.Ho) * static_cast<uint32_t>(s.Wo);
+    division_constants(wa.hw, wa.hw_mul, wa.hw_shift);
+    division_constants(static_cast<uint32_t>(s.Wo), wa.wo_mul, wa.wo_shift);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, res, wa, w, y, s.Cout,
                        s.K, static_cast<int>(total_pix), groups_per_tile, n_ranges, base_groups,
                        rem_groups, tail_first, tail_base, tail_rem, thr, flip);
     return hipGetLastError();
@@ -598,6 +654,10 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
                                         uint64_t* bits)                                           \
     {                                                                                             \
         const ResArgs res{scale, shift, r, x_out, reinterpret_cast<uint16_t*>(bits)};             \
+        /* one word per pixel: the epilogue's r and z traffic dominates and 128-byte runs pay */  \
+        if (CW == 1 && env_int("DABNN_AREG_RES_CG", 32) == 32)                                    \
+            return launch_areg_inst<CW, S, kRes32>(a, w, nullptr, s, stream, nullptr, nullptr,    \
+                                                   res);                                          \
         return launch_areg_inst<CW, S, kRes>(a, w, nullptr, s, stream, nullptr, nullptr, res);    \
     }
 

@@ -158,6 +158,14 @@ def test_bconv2d_bn_residual_work_split(dabnn, oracle, slots, monkeypatch):
     test_bconv2d_bn_residual(dabnn, oracle, (3, 9, 7, 64, 192, 3, 2, 1), False)
 
 
+def test_bconv2d_bn_residual_sixteen_channel_groups_forced(dabnn, oracle, monkeypatch):
+    """One-word-per-pixel layers default to 32-channel groups in the fused block kernel; the
+    16-channel variant of the same shapes through the test hook."""
+    monkeypatch.setenv("DABNN_AREG_RES_CG", "16")
+    for shape in [(1, 14, 14, 64, 64, 3, 1, 1), (5, 57, 30, 64, 64, 3, 1, 1), (3, 11, 10, 64, 128, 3, 2, 1)]:
+        test_bconv2d_bn_residual(dabnn, oracle, shape, True)
+
+
 def test_bconv2d_bn_residual_full_batch_layer(dabnn, oracle):
     """Batch 256 at a benchmark shape: sampled pixels (all channels) against the oracle chain, and
     the whole result against the library's own two-call sequence."""
