@@ -220,6 +220,42 @@ def main():
             chain_ms.append((time.perf_counter() - t6) * 1e3 / k_chain)
         del zs, bits_out, down
 
+    # Batch-1 latency of the dependent 16-block chain (the paper's deployment case is one image
+    # at a time): launch-bound, so it is also replayed from a HIP graph.
+    lat = None
+    if all(L.Cout % 64 == 0 for L in layers):
+        a1 = torch.zeros((1, layers[0].H, layers[0].W, layers[0].Cin // 64), dtype=torch.int64, device="cuda")
+        z1 = [torch.empty((1, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
+        b1 = [torch.empty((1, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
+        d1 = {li: torch.randn((1, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
+              if li == 0 or L.stride != 1}
+        sc1 = [torch.full((L.Cout,), 1.0 / (L.K ** 0.5), dtype=torch.float32, device="cuda") for L in layers]
+        sh1 = [torch.zeros((L.Cout,), dtype=torch.float32, device="cuda") for L in layers]
+
+        def one_image():
+            a_in = a1
+            for li, L in enumerate(layers):
+                r = d1[li] if li in d1 else z1[li - 1]
+                binding.bconv2d_bn_residual(a_in, wps[li], sc1[li], sh1[li], r, L.Cin, L.stride, 1,
+                                            x_out=z1[li], out=b1[li])
+                a_in = b1[li]
+
+        def wall_us(f, reps=200):
+            f()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                f()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) * 1e6 / reps
+        eager_us = wall_us(one_image)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_image()
+        lat = {"what": "16 dependent blocks (dabnn_bconv2d_bn_residual) on one 224x224 image's feature maps",
+               "eager_us": round(eager_us, 1), "hip_graph_replay_us": round(wall_us(graph.replay), 1)}
+        del graph
+
     # The largest bit-pack shape of the parity configs (benchmark configs[2]: 256x56x56x256,
     # 822 MB of fp32), far beyond the 256 MB Infinity Cache: the launch the HBM fraction of the
     # bit-pack kernel is claimed on.  One HIP-event pair per launch.
@@ -319,6 +355,8 @@ def main():
             "one_call_per_block_ms_per_step": round(chain_ms[1], 4),   # dabnn_bconv2d_bn_residual
             "one_call_per_block_GOPS": round(total_ops / (chain_ms[1] * 1e-3) / 1e9, 1),
         }
+    if lat is not None:
+        result["batch1_chain_latency"] = lat
     if big is not None:
         result["roofline_bitpack"]["largest_launch"] = big
     if mfma_ms is not None:
