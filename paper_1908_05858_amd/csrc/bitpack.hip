@@ -82,6 +82,84 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_kernel(
         out[g0 + lane] = make_uint2(lo, hi);
 }
 
+// C not a multiple of 64.  Rows are then not aligned to the 256-byte runs a wavefront reads best,
+// and a pixel's last word has only C % 64 real channels.  Instead of reading row by row with
+// masked lanes, the tensor is read as ONE flat stream of floats in aligned 64-element chunks
+// (every load a full coalesced 256-byte run); each chunk's 64 sign bits form a ballot, and an
+// output word is a bit-field of that flat bit stream: word (p, j) starts at flat bit p*C + 64*j
+// and is min(64, C - 64*j) bits long.  A wavefront produces 32 consecutive output words: it loads
+// the (at most 33) chunks they touch, parks ballot k in lane k, and lane w then assembles word w
+// from two neighbouring ballots with a funnel shift and a length mask.
+constexpr int kTailWords = 32;
+
+template <int MODE>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
+    const uint32_t* __restrict__ x, uint2* __restrict__ out, int64_t n_words, int64_t n_floats,
+    int C, int Cw)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t w0 =
+        (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block) * kTailWords;
+    if (w0 >= n_words)
+        return;
+    // flat bit range [s0, e1) of this wavefront's words, and the chunks that cover it
+    const int64_t p0 = w0 / Cw;
+    const int64_t s0 = p0 * C + 64 * (w0 - p0 * Cw);
+    const int64_t w1 = min(w0 + kTailWords, n_words) - 1;
+    const int64_t p1 = w1 / Cw;
+    const int64_t j1 = w1 - p1 * Cw;
+    const int64_t e1 = p1 * C + min<int64_t>(64 * j1 + 64, C);
+    const int64_t c_first = s0 >> 6;
+    const int n_chunks = static_cast<int>(((e1 - 1) >> 6) - c_first) + 1;  // <= kTailWords + 1
+
+    uint32_t v[kTailWords + 1];
+#pragma unroll
+    for (int k = 0; k <= kTailWords; ++k) {
+        // always a valid address (no branch around the load, so all 33 stay in flight); chunks
+        // and elements past the end are zeroed afterwards
+        const int64_t idx = (c_first + k) * 64 + lane;
+        v[k] = __builtin_nontemporal_load(x + min(idx, n_floats - 1));
+    }
+#pragma unroll
+    for (int k = 0; k <= kTailWords; ++k) {
+        const int64_t idx = (c_first + k) * 64 + lane;
+        v[k] = (k < n_chunks && idx < n_floats) ? v[k] : 0u;
+    }
+    uint32_t blo = 0, bhi = 0;  // lane k: the sign bits of chunk c_first + k
+    static_for<0, kTailWords + 1>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        const uint64_t word = __builtin_amdgcn_ballot_w64(negative_bit<MODE>(v[k]));
+        if (lane == k) {
+            blo = static_cast<uint32_t>(word);
+            bhi = static_cast<uint32_t>(word >> 32);
+        }
+    });
+
+    // lane w < 32 assembles output word w0 + w; all of it in 32-bit arithmetic relative to the
+    // wavefront's first pixel (64-bit divisions happen once per wavefront, above, on scalars)
+    const int j0 = static_cast<int>(w0 - p0 * Cw);
+    const int base = static_cast<int>(p0 * C - c_first * 64);  // flat bit of pixel p0, chunk-relative
+    const int last = static_cast<int>(w1 - w0);
+    const int q = j0 + min(lane & (kTailWords - 1), last);
+    const int dp = q / Cw;
+    const int j = q - dp * Cw;
+    const int rel = base + dp * C + 64 * j;  // 0 <= rel < 64 * (kTailWords + 1)
+    const int src = rel >> 6, off = rel & 63;
+    const int len = min(64, C - 64 * j);
+    const uint64_t b0 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(static_cast<int>(bhi), src))) << 32) |
+                        static_cast<uint32_t>(__shfl(static_cast<int>(blo), src));
+    const uint64_t b1 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(static_cast<int>(bhi), src + 1))) << 32) |
+                        static_cast<uint32_t>(__shfl(static_cast<int>(blo), src + 1));
+    uint64_t word = b0 >> off;
+    if (off != 0)
+        word |= b1 << (64 - off);
+    if (len < 64)
+        word &= (uint64_t{1} << len) - 1;  // bits past the pixel's last channel are 0
+    if (lane < kTailWords && w0 + lane < n_words)
+        out[w0 + lane] = make_uint2(static_cast<uint32_t>(word), static_cast<uint32_t>(word >> 32));
+}
+
 // Fused batch-norm + shortcut + sign + bit-pack between two binary convolutions (Sec. 2.1.1 names
 // the fused BN-binarization layer; Sec. 2.3's Bi-Real blocks add a real-valued shortcut first):
 //   z = ((scale[c] * float(y)) + shift[c]) + r,  every operation rounded separately (no FMA),
@@ -257,6 +335,18 @@ hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, 
     uint2* o = reinterpret_cast<uint2*>(out);
     const bool flat = (C % 64) == 0;
     const int cw = static_cast<int>(Cw);
+    if (!flat && env_int("DABNN_BITPACK_ROWWISE", 0) == 0) {  // test hook: the row-wise tail kernel
+        const int64_t per_block_t = static_cast<int64_t>(kTailWords) * kWavesPerBlock;
+        const int64_t blocks_t = (n_words + per_block_t - 1) / per_block_t;
+        if (blocks_t > 0x7fffffffLL)
+            return hipErrorInvalidValue;
+        const dim3 grid_t(static_cast<unsigned>(blocks_t));
+        if (sign_mode == 0)
+            bitpack_tail_kernel<0><<<grid_t, block, 0, stream>>>(xi, o, n_words, n_rows * C, C, cw);
+        else
+            bitpack_tail_kernel<1><<<grid_t, block, 0, stream>>>(xi, o, n_words, n_rows * C, C, cw);
+        return hipGetLastError();
+    }
     if (sign_mode == 0) {
         if (flat)
             bitpack_kernel<0, true><<<grid, block, 0, stream>>>(xi, o, n_words, C, cw);

@@ -60,6 +60,26 @@ def test_bitpack_ragged(dabnn, oracle, C, n_pixels):
         assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
 
 
+def test_bitpack_rowwise_tail_kernel_forced(dabnn, oracle, monkeypatch):
+    """Channel counts that are not multiples of 64 default to the flat-stream kernel; the row-wise
+    kernel of the same shapes through the library's test hook."""
+    monkeypatch.setenv("DABNN_BITPACK_ROWWISE", "1")
+    for n_pixels, C in [(1, 1), (5, 3), (63, 65), (1025, 80), (64, 200), (77, 1000)]:
+        x = wl.inject_zeros(wl.activations((n_pixels, C), 4300 + C), 4301 + C)
+        for mode in (0, 1):
+            assert np.array_equal(words(dabnn.bitpack(gpu(x), sign_mode=mode)), oracle.bitpack(x, mode))
+
+
+@pytest.mark.parametrize("C", [1, 2, 31, 33, 63, 65, 96, 127, 129, 191, 320, 1000, 4097])
+def test_bitpack_flat_stream_tail_kernel(dabnn, oracle, C):
+    """Pixel counts around the 32-words-per-wavefront and 4-wavefronts-per-block boundaries."""
+    Cw = (C + 63) // 64
+    for n_words in (1, 31, 32, 33, 127, 128, 129, 4 * 32 * 7 + 5):
+        n_pixels = max(1, n_words // Cw)
+        x = wl.inject_zeros(wl.activations((n_pixels, C), 4400 + C + n_pixels), 4401 + C)
+        assert np.array_equal(words(dabnn.bitpack(gpu(x))), oracle.bitpack(x)), (n_pixels, C)
+
+
 def test_bitpack_special_values(dabnn, oracle):
     row = wl.special_values()
     x = np.tile(row, (3, 13))[:, :200].copy()       # C = 200: specials in every word, with a tail
