@@ -769,3 +769,27 @@ def test_random_shapes_every_entry_point(dabnn, oracle, shape):
     if Cin % 64 == 0 and Cout % 64 == 0:
         y8 = dabnn.bconv2d_int8(dabnn.expand_int8(a, Cin), dabnn.expand_int8(wp, Cin), stride, pad)
         assert np.array_equal(y8.cpu().numpy(), want)
+
+
+def test_results_are_identical_run_to_run(dabnn):
+    """Integer outputs and packed words must not depend on scheduling: five runs of every tuned
+    kernel family on a shape that spans many wavefronts, compared byte for byte."""
+    x = gpu(wl.activations((16, 28, 28, 128), 8800))
+    wf = gpu(wl.weights((128, 3, 3, 128), 8801))
+    gamma, beta, mean, var = _bn_params(128, 8802)
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * 128)
+    r = gpu(wl.activations((16, 28, 28, 128), 8803))
+    sc = torch.full((128,), 0.03, device="cuda")
+    sh = torch.zeros(128, device="cuda")
+    first = None
+    for rep in range(5):
+        a = dabnn.bitpack(x)
+        wp = dabnn.pack_weights(wf)
+        outs = [a, dabnn.bconv2d(a, wp, 128, 1, 1, algo=3), dabnn.bconv2d(a, wp, 128, 1, 1, algo=2),
+                dabnn.bconv2d_bnsign(a, wp, thr, flip, 128, 1, 1)]
+        z, bits = dabnn.bconv2d_bn_residual(a, wp, sc, sh, r, 128, 1, 1)
+        outs += [z.view(torch.int32), bits]
+        if first is None:
+            first = [o.clone() for o in outs]
+        else:
+            assert all(torch.equal(o, f) for o, f in zip(outs, first)), rep
