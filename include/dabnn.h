@@ -10,8 +10,17 @@
  *     allocates, frees, copies to the host or synchronises.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates
  *     its arguments on the host, enqueues its kernel(s) on `stream` and returns at once.
- *   - Return value: a dabnn_status (0 = DABNN_OK).  On any error nothing is launched and no
- *     output byte is written.  No exception crosses the boundary.
+ *   - Return value: a dabnn_status (0 = DABNN_OK).  An argument error (status 1-4) is found on
+ *     the host before anything is launched: no output byte is written.  DABNN_ERR_LAUNCH means
+ *     the HIP runtime refused a launch; the calls that enqueue two kernels
+ *     (dabnn_bconv2d_zeropad with pad > 0, and dabnn_bconv2d_bn_residual on shapes outside its
+ *     fused kernel) may then already have enqueued the first, so their outputs are undefined.
+ *     No exception crosses the boundary.
+ *   - The first call that reaches a given kernel asks the HIP runtime once for that kernel's
+ *     occupancy (hipOccupancyMaxActiveBlocksPerMultiprocessor) and the device's CU count; the
+ *     answers are cached for the life of the process.  Under stream capture, call each entry
+ *     point once eagerly beforehand.
+ *   - The library reads no environment variable.  dabnn_set_option is the only switch.
  *   - Tensors are dense, row-major, in the layouts stated per call.  Input and output buffers
  *     of one call must not overlap.
  *   - Bit convention (shared by activations and weights): bit 1 <-> value -1, bit 0 <-> +1;
@@ -58,6 +67,30 @@ typedef enum {
     DABNN_BGEMM_SIGNED = 0,  /* sum_k A_ik * B_jk over +-1 values = 2*C_ij - K (what the convolutions return) */
     DABNN_BGEMM_MATCHES = 1  /* C_ij of Eq. 1 as printed: bitcount(xnor), the number of agreeing bits */
 } dabnn_bgemm_mode;
+
+/*
+ * Tuning and test options.  Every option is 0 by default, which means "the library chooses";
+ * production code has no reason to set any.  They exist so that tests can reach every kernel
+ * variant and every work split on any shape.  Values are process-wide, read at each call with
+ * relaxed atomic loads; setting one while another thread is inside a call affects either that
+ * call or the next.
+ */
+typedef enum {
+    DABNN_OPT_AREG_SLOTS = 0,      /* n > 0: split DABNN_ALGO_AREG work as if the device had n resident wavefronts */
+    DABNN_OPT_AREG_TAIL = 1,       /* uneven remainder of the split as small pieces: 1 never, 2 always */
+    DABNN_OPT_AREG_STORE = 2,      /* output store of DABNN_ALGO_AREG: 1 direct 16-byte stores, 16 or 32
+                                      channels transposed through LDS (ignored if Cout is no multiple) */
+    DABNN_OPT_RES_CHANNELS = 3,    /* 16: 16-channel groups in dabnn_bconv2d_bn_residual's fused kernel */
+    DABNN_OPT_WREG_PIXELS = 4,     /* 7 or 8: output pixels per task of DABNN_ALGO_WREG */
+    DABNN_OPT_BGEMM_COLUMNS = 5,   /* 16: 16-column groups in dabnn_bgemm's fast kernel */
+    DABNN_OPT_BITPACK_ROWWISE = 6, /* 1: the row-wise kernel for channel counts that are no multiple of 64 */
+    DABNN_OPT_COUNT = 7
+} dabnn_option;
+
+/* Sets option `option` (a dabnn_option) to `value` and returns DABNN_OK, or DABNN_ERR_UNSUPPORTED
+ * for an unknown option or a negative value.  dabnn_get_option returns the current value, or -1. */
+int dabnn_set_option(int option, int value);
+int dabnn_get_option(int option);
 
 /* ceil(C / 64): 64-bit words per pixel for C channels.  Returns -1 if C <= 0. */
 int64_t dabnn_packed_words(int64_t C);
@@ -122,6 +155,7 @@ int dabnn_bn_sign_pack(const int32_t *y, const float *scale, const float *shift,
  *   r            : f32 [N][Ho][Wo][Cout] device or NULL (no shortcut)
  *   x_out        : f32 [N][Ho][Wo][Cout] device, required (it doubles as the staging buffer of the
  *                  int32 result for shapes the fused kernel does not cover); must not alias r
+ *                  (dabnn_bn_sign_pack allows x_out == r; this call does not)
  *   bits         : u64 [N][Ho][Wo][ceil(Cout/64)] device, tail bits 0
  * The fused kernel runs 3x3 kernels, stride 1 or 2, ceil(Cin/64) in {1,2,4,8}, Cout % 64 == 0,
  * a shortcut, and scale, shift, r, x_out 16-byte aligned; every other valid case runs as the two kernels in sequence.

@@ -55,6 +55,8 @@ def load():
     lib.dabnn_bconv2d_bnsign.argtypes, lib.dabnn_bconv2d_bnsign.restype = [vp] * 5 + [i32] * 9 + [vp], i32
     lib.dabnn_bn_thresholds.argtypes = [vp] * 4 + [ctypes.c_float, i32, i32, vp, vp]
     lib.dabnn_bn_thresholds.restype = i32
+    lib.dabnn_set_option.argtypes, lib.dabnn_set_option.restype = [i32, i32], i32
+    lib.dabnn_get_option.argtypes, lib.dabnn_get_option.restype = [i32], i32
     _lib = lib
     return lib
 
@@ -63,7 +65,20 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_bconv2d", "dabnn_bconv2d_algo", "dabnn_bconv2d_pick_algo", "dabnn_status_string",
            "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
            "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
-           "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack", "dabnn_bconv2d_bn_residual"]
+           "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack", "dabnn_bconv2d_bn_residual",
+           "dabnn_set_option", "dabnn_get_option"]
+
+(OPT_AREG_SLOTS, OPT_AREG_TAIL, OPT_AREG_STORE, OPT_RES_CHANNELS, OPT_WREG_PIXELS, OPT_BGEMM_COLUMNS,
+ OPT_BITPACK_ROWWISE) = range(7)
+
+
+def set_option(option, value):
+    """Tuning / test switch of the library (a dabnn_option); 0 restores the default."""
+    _check(load().dabnn_set_option(option, value), "dabnn_set_option")
+
+
+def get_option(option):
+    return load().dabnn_get_option(option)
 
 
 def status_string(status):

@@ -31,9 +31,15 @@ def build_library(verbose=False):
         cmd = [hipcc] + HIPCC_FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((cmd, subprocess.Popen(cmd)))
+        procs.append((cmd, subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True)))
     for cmd, p in procs:
-        if p.wait() != 0:
+        _, err = p.communicate()
+        # hipcc's host pass does not know the device-only feature switch above and says so once
+        # per translation unit; everything else it prints is shown
+        err = "".join(l for l in err.splitlines(True) if "'-packed-fp32-ops' is not a recognized feature" not in l)
+        if err.strip():
+            print(err, end="", flush=True)
+        if p.returncode != 0:
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
     link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH]
     if verbose:

@@ -328,13 +328,7 @@ hipError_t launch_wreg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
                             hipStream_t stream)
 {
     auto kernel = bconv3x3_wreg_kernel<CW, S, P>;
-    static int blocks_per_cu = 0;
-    if (blocks_per_cu == 0) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb <= 0)
-            nb = 2;
-        blocks_per_cu = nb;
-    }
+    static const int blocks_per_cu = resident_blocks_per_cu(kernel);
     const int chunks = (s.Wo + P - 1) / P;
     const int64_t n_tasks64 = static_cast<int64_t>(s.N) * s.Ho * chunks;
     if (n_tasks64 > 0x3fffffff)
@@ -366,7 +360,7 @@ hipError_t launch_wreg_p(const uint32_t* a, const uint32_t* w, int32_t* y, const
     const int waste8 = (s.Wo + 7) / 8 * 8 - s.Wo;
     const int waste7 = (s.Wo + 6) / 7 * 7 - s.Wo;
     int p = (waste7 < waste8) ? 7 : 8;
-    const int forced = env_int("DABNN_WREG_P", 0);  // test hook: force the chunk width
+    const int forced = option(DABNN_OPT_WREG_PIXELS);  // 0: as above; 7 or 8 forces the chunk width
     if (forced == 7 || forced == 8)
         p = forced;
     if (p == 7)

@@ -18,13 +18,15 @@ DABNN_DECLARE(1, 1) DABNN_DECLARE(1, 2) DABNN_DECLARE(2, 1) DABNN_DECLARE(2, 2)
 DABNN_DECLARE(4, 1) DABNN_DECLARE(4, 2) DABNN_DECLARE(8, 1) DABNN_DECLARE(8, 2)
 #undef DABNN_DECLARE
 
-// The kernels address the activation tensor and (on the direct-store path) the output with
-// 32-bit element offsets.
+// The kernels address a window tap as the tensor base plus a 32-bit BYTE offset, and (on the
+// direct-store path) the output with 32-bit element offsets: the packed activation tensor must
+// stay below 4 GiB and the output below 2^31 elements.  Larger tensors run the other families,
+// which index with size_t.
 static bool areg_offsets_fit(const ConvShape& s)
 {
-    const int64_t act_dwords = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 2;
+    const int64_t act_bytes = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 8;
     const int64_t out_elems = static_cast<int64_t>(s.N) * s.Ho * s.Wo * s.Cout;
-    return act_dwords < (int64_t{1} << 31) && out_elems < (int64_t{1} << 31);
+    return act_bytes < (int64_t{1} << 32) && out_elems < (int64_t{1} << 31);
 }
 
 bool bconv_bnsign_areg_supports(const ConvShape& s)

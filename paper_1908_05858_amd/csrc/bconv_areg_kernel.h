@@ -579,7 +579,7 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     // Exactly the resident wavefront slots; every wavefront gets the same number of groups
     // (+-1), so the launch is one balanced round.
     int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
-    const int forced_slots = env_int("DABNN_AREG_SLOTS", 0);  // test hook: pretend a smaller chip
+    const int forced_slots = option(DABNN_OPT_AREG_SLOTS);  // > 0: pretend a chip with that many slots
     if (forced_slots > 0)
         ranges = forced_slots;
     if (ranges > n_groups)
@@ -593,9 +593,9 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     // 6 % of the wavefronts); a large remainder is cheaper as whole groups, because the pieces
     // use the slower direct store and each needs its own window.
     int tail_first = 0, tail_base = 0, tail_rem = 0;
-    const int tail_mode = env_int("DABNN_AREG_TAIL", 1);  // test hook: 0 never, 2 always
-    if (TR == kTailTR && rem_groups > 0 &&
-        (tail_mode == 2 || (tail_mode == 1 && rem_groups * 4 <= n_ranges))) {
+    const int tail_mode = option(DABNN_OPT_AREG_TAIL);  // 0 by size, 1 never, 2 always
+    if (TR == kTailTR && rem_groups > 0 && tail_mode != 1 &&
+        (tail_mode == 2 || rem_groups * 4 <= n_ranges)) {
         constexpr int pieces = G::CG / AregGeom<CW, 0>::CG;
         const int n_tail = rem_groups * pieces;
         tail_first = base_groups * n_ranges * pieces;
@@ -623,8 +623,10 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     // write traffic) is the faster choice at the Bi-Real-18 shapes.  With 8 words per pixel
     // (K = 4608) the output rate is so low that the direct store wins.
     int tr = (CW <= 4 && s.Cout % 16 == 0) ? 16 : 0;
-    const int forced = env_int("DABNN_AREG_TR", -1);  // test hook: force the store variant
-    if (forced == 0 || (forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
+    const int forced = option(DABNN_OPT_AREG_STORE);  // 0 as above, 1 direct, 16 / 32 transposed
+    if (forced == 1)
+        tr = 0;
+    else if ((forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
         tr = forced;
     if (tr == 32) return launch_areg_inst<CW, S, 32>(a, w, y, s, stream);
     if (tr == 16) return launch_areg_inst<CW, S, 16>(a, w, y, s, stream);
@@ -655,7 +657,7 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     {                                                                                             \
         const ResArgs res{scale, shift, r, x_out, reinterpret_cast<uint16_t*>(bits)};             \
         /* one word per pixel: the epilogue's r and z traffic dominates and 128-byte runs pay */  \
-        if (CW == 1 && env_int("DABNN_AREG_RES_CG", 32) == 32)                                    \
+        if (CW == 1 && option(DABNN_OPT_RES_CHANNELS) != 16)                                    \
             return launch_areg_inst<CW, S, kRes32>(a, w, nullptr, s, stream, nullptr, nullptr,    \
                                                    res);                                          \
         return launch_areg_inst<CW, S, kRes>(a, w, nullptr, s, stream, nullptr, nullptr, res);    \

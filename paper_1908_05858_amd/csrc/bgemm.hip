@@ -275,7 +275,7 @@ hipError_t launch_rowreg(const uint32_t* A, const uint32_t* B, int32_t* C, int64
     // With short rows the product is bound by the int32 output: 32 columns per group make every
     // store a whole 128-byte line.  Long rows keep 16 columns (fewer registers, finer work split).
     if constexpr (KD <= 16) {
-        if (N % 32 == 0 && env_int("DABNN_BGEMM_CG", 32) == 32)  // test hook: force 16 columns
+        if (N % 32 == 0 && option(DABNN_OPT_BGEMM_COLUMNS) != 16)  // test hook: force 16 columns
             return launch_rowreg_cg<KD, 32>(A, B, C, M, N, K, mode, stream);
     }
     return launch_rowreg_cg<KD, 16>(A, B, C, M, N, K, mode, stream);

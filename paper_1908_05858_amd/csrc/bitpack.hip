@@ -169,9 +169,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
 // Bound by HBM: 4 (y) + 4 (r) + 4 (z) + 1/8 bytes per element.
 template <bool HAS_R, bool HAS_X, bool FLAT>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void bn_sign_pack_kernel(
-    const int32_t* __restrict__ y, const float* __restrict__ scale, const float* __restrict__ shift,
-    const float* __restrict__ r, float* __restrict__ x_out, uint2* __restrict__ out,
-    int64_t n_words, int C, int Cw)
+    // y, r and x_out carry no __restrict__: x_out may be r's storage, or y's (the two-kernel route
+    // of dabnn_bconv2d_bn_residual stages y there); every element is read before it is written
+    const int32_t* y, const float* __restrict__ scale, const float* __restrict__ shift,
+    const float* r, float* x_out, uint2* __restrict__ out, int64_t n_words, int C, int Cw)
 {
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -336,7 +337,7 @@ hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, 
     uint2* o = reinterpret_cast<uint2*>(out);
     const bool flat = (C % 64) == 0;
     const int cw = static_cast<int>(Cw);
-    if (!flat && env_int("DABNN_BITPACK_ROWWISE", 0) == 0) {  // test hook: the row-wise tail kernel
+    if (!flat && option(DABNN_OPT_BITPACK_ROWWISE) == 0) {  // test hook: the row-wise tail kernel
         const int64_t per_block_t = static_cast<int64_t>(kTailWords) * kWavesPerBlock;
         const int64_t blocks_t = (n_words + per_block_t - 1) / per_block_t;
         if (blocks_t > 0x7fffffffLL)

@@ -6,7 +6,21 @@
 
 #include "launch.h"
 
+#include "kernel_util.h"
+
+#include <atomic>
 #include <cmath>
+
+namespace dabnn {
+
+static std::atomic<int> g_options[DABNN_OPT_COUNT];  // zero-initialised: "the library chooses"
+
+int option(int id)
+{
+    return g_options[id].load(std::memory_order_relaxed);
+}
+
+}  // namespace dabnn
 
 namespace {
 
@@ -72,6 +86,21 @@ int pick_algo(const dabnn::ConvShape& s, const void* y)
 }  // namespace
 
 extern "C" {
+
+int dabnn_set_option(int option, int value)
+{
+    if (option < 0 || option >= DABNN_OPT_COUNT || value < 0)
+        return DABNN_ERR_UNSUPPORTED;
+    dabnn::g_options[option].store(value, std::memory_order_relaxed);
+    return DABNN_OK;
+}
+
+int dabnn_get_option(int option)
+{
+    if (option < 0 || option >= DABNN_OPT_COUNT)
+        return -1;
+    return dabnn::option(option);
+}
 
 int64_t dabnn_packed_words(int64_t C)
 {

@@ -3,7 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <cstdlib>
+#include "../../include/dabnn.h"
+
 #include <type_traits>
 
 namespace dabnn {
@@ -30,23 +31,19 @@ __device__ __forceinline__ void schedule_fence()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-inline int env_int(const char* name, int fallback)
-{
-    const char* e = std::getenv(name);
-    return e ? std::atoi(e) : fallback;
-}
+// Tuning and test options (dabnn_set_option in the C ABI; ids are the dabnn_option values).
+// The library never reads the environment: an option has its default until a caller sets it.
+int option(int id);
 
 inline int device_cu_count()
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0)
-            cus = 256;
-    }
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        return n;
+    }();
     return cus;
 }
 

@@ -85,6 +85,35 @@ def test_pick_algo(lib):
     assert lib.dabnn_bconv2d_pick_algo(1, 56, 56, 64, 64, 3, 3, 0, 1) == -1
 
 
+def test_tensors_past_the_32bit_byte_offsets_leave_the_activation_stationary_family(lib):
+    """The activation-stationary kernels address window taps with 32-bit byte offsets: a packed
+    activation tensor of 4 GiB or more must be routed to a family that indexes with size_t."""
+    AREG = 3
+    # 8200 x 8200 pixels x 8 words = 4.30 GB of packed activations (below 2^31 words: a valid shape)
+    assert lib.dabnn_bconv2d_pick_algo(1, 8200, 8200, 512, 16, 3, 3, 1, 1) not in (AREG, -1)
+    # the same tensor with a channel count the fused modes would take (Cout % 64 == 0), stride 2
+    assert lib.dabnn_bconv2d_pick_algo(1, 8200, 8200, 512, 64, 3, 3, 2, 1) not in (AREG, -1)
+    # just below the limit the family is still used: 8192 x 8191 x 8 words x 8 B < 2^32
+    assert lib.dabnn_bconv2d_pick_algo(1, 8192, 8191, 512, 16, 3, 3, 1, 1) == AREG
+    assert lib.dabnn_bconv2d_pick_algo(1, 8192, 8192, 512, 16, 3, 3, 1, 1) != AREG
+
+
+def test_options(lib):
+    """Options default to 0, are set and read back through the C ABI, and unknown ones are refused;
+    the library ignores the environment."""
+    import os
+    for opt in range(7):
+        assert lib.dabnn_get_option(opt) == 0
+    assert lib.dabnn_set_option(2, 16) == 0 and lib.dabnn_get_option(2) == 16
+    assert lib.dabnn_set_option(2, 0) == 0 and lib.dabnn_get_option(2) == 0
+    assert lib.dabnn_set_option(7, 1) == 4 and lib.dabnn_set_option(-1, 1) == 4
+    assert lib.dabnn_set_option(0, -5) == 4
+    assert lib.dabnn_get_option(7) == -1
+    src = os.path.join(ROOT, "paper_1908_05858_amd", "csrc")
+    for name in os.listdir(src):
+        assert "getenv" not in open(os.path.join(src, name)).read(), name
+
+
 def test_bn_thresholds_match_fp64_batch_norm_for_every_integer(lib):
     """The host helper, exhaustively: for every integer y in [-K, K] the threshold rule equals
     the sign of the fp64 batch-norm (numpy, evaluated in the same order)."""

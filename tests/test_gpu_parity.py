@@ -22,6 +22,19 @@ def dabnn():
     return binding
 
 
+@pytest.fixture
+def option(dabnn):
+    """Sets tuning/test options of the library for one test and restores the defaults after."""
+    touched = []
+
+    def set_(opt, value):
+        touched.append(opt)
+        dabnn.set_option(opt, value)
+    yield set_
+    for opt in touched:
+        dabnn.set_option(opt, 0)
+
+
 def gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -60,10 +73,10 @@ def test_bitpack_ragged(dabnn, oracle, C, n_pixels):
         assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
 
 
-def test_bitpack_rowwise_tail_kernel_forced(dabnn, oracle, monkeypatch):
+def test_bitpack_rowwise_tail_kernel_forced(dabnn, oracle, option):
     """Channel counts that are not multiples of 64 default to the flat-stream kernel; the row-wise
-    kernel of the same shapes through the library's test hook."""
-    monkeypatch.setenv("DABNN_BITPACK_ROWWISE", "1")
+    kernel of the same shapes through the library's option."""
+    option(dabnn.OPT_BITPACK_ROWWISE, 1)
     for n_pixels, C in [(1, 1), (5, 3), (63, 65), (1025, 80), (64, 200), (77, 1000)]:
         x = wl.inject_zeros(wl.activations((n_pixels, C), 4300 + C), 4301 + C)
         for mode in (0, 1):
@@ -172,16 +185,16 @@ def test_bconv2d_bn_residual(dabnn, oracle, shape, with_r):
 
 
 @pytest.mark.parametrize("slots", [1, 5, 64])
-def test_bconv2d_bn_residual_work_split(dabnn, oracle, slots, monkeypatch):
-    monkeypatch.setenv("DABNN_AREG_SLOTS", str(slots))
+def test_bconv2d_bn_residual_work_split(dabnn, oracle, slots, option):
+    option(dabnn.OPT_AREG_SLOTS, slots)
     test_bconv2d_bn_residual(dabnn, oracle, (2, 14, 14, 128, 128, 3, 1, 1), True)
     test_bconv2d_bn_residual(dabnn, oracle, (3, 9, 7, 64, 192, 3, 2, 1), False)
 
 
-def test_bconv2d_bn_residual_sixteen_channel_groups_forced(dabnn, oracle, monkeypatch):
+def test_bconv2d_bn_residual_sixteen_channel_groups_forced(dabnn, oracle, option):
     """One-word-per-pixel layers default to 32-channel groups in the fused block kernel; the
-    16-channel variant of the same shapes through the test hook."""
-    monkeypatch.setenv("DABNN_AREG_RES_CG", "16")
+    16-channel variant of the same shapes through the library's option."""
+    option(dabnn.OPT_RES_CHANNELS, 16)
     for shape in [(1, 14, 14, 64, 64, 3, 1, 1), (5, 57, 30, 64, 64, 3, 1, 1), (3, 11, 10, 64, 128, 3, 2, 1)]:
         test_bconv2d_bn_residual(dabnn, oracle, shape, True)
 
@@ -324,14 +337,14 @@ def test_odd_shapes_tuned(dabnn, oracle, shape, algo):
     run_conv(dabnn, oracle, *shape, seed=999 + sum(shape), algo=algo)
 
 
-@pytest.mark.parametrize("env", [("DABNN_AREG_TR", "0", 3), ("DABNN_AREG_TR", "16", 3), ("DABNN_AREG_TR", "32", 3),
-                                 ("DABNN_WREG_P", "7", 2), ("DABNN_WREG_P", "8", 2)],
+@pytest.mark.parametrize("env", [("OPT_AREG_STORE", 1, 3), ("OPT_AREG_STORE", 16, 3), ("OPT_AREG_STORE", 32, 3),
+                                 ("OPT_WREG_PIXELS", 7, 2), ("OPT_WREG_PIXELS", 8, 2)],
                          ids=lambda e: f"{e[0]}={e[1]}")
-def test_kernel_variants(dabnn, oracle, env, monkeypatch):
+def test_kernel_variants(dabnn, oracle, env, option):
     """Every store variant of the activation-stationary family and both chunk widths of the
-    filter-stationary family, forced through the library's test hooks."""
+    filter-stationary family, forced through the library's options."""
     name, value, algo = env
-    monkeypatch.setenv(name, value)
+    option(getattr(dabnn, name), value)
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
                   (2, 7, 7, 512, 64, 3, 1, 1), (1, 57, 30, 64, 32, 3, 1, 1)]:
         print("variant", env, shape, flush=True)
@@ -339,13 +352,13 @@ def test_kernel_variants(dabnn, oracle, env, monkeypatch):
 
 
 @pytest.mark.parametrize("slots", [1, 3, 7, 40, 1000])
-@pytest.mark.parametrize("tail", ["0", "2"])
-def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, monkeypatch):
+@pytest.mark.parametrize("tail", [1, 2])
+def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, option):
     """The split of (tile, channel group) pairs over wavefronts, with the wavefront count forced
     small so that ranges span several tiles, and the uneven remainder handed out either as whole
     groups or as direct-store pieces."""
-    monkeypatch.setenv("DABNN_AREG_SLOTS", str(slots))
-    monkeypatch.setenv("DABNN_AREG_TAIL", tail)
+    option(dabnn.OPT_AREG_SLOTS, slots)
+    option(dabnn.OPT_AREG_TAIL, tail)
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
                   (1, 23, 17, 64, 48, 3, 1, 1), (2, 7, 7, 512, 64, 3, 1, 1)]:
         print("split", slots, tail, shape, flush=True)
@@ -431,10 +444,10 @@ def test_bgemm(dabnn, oracle, shape, mode):
     assert np.array_equal(C.cpu().numpy(), want)
 
 
-def test_bgemm_sixteen_column_groups_forced(dabnn, oracle, monkeypatch):
+def test_bgemm_sixteen_column_groups_forced(dabnn, oracle, option):
     """Short rows default to 32-column groups (whole 128-byte stores); the 16-column kernel of the
-    same shapes through the library's test hook."""
-    monkeypatch.setenv("DABNN_BGEMM_CG", "16")
+    same shapes through the library's option."""
+    option(dabnn.OPT_BGEMM_COLUMNS, 16)
     for M, N, K in [(200, 64, 64), (1000, 32, 128), (300, 128, 512), (4100, 256, 64)]:
         xa = wl.activations((M, K), 883 + M)
         xb = wl.weights((N, K), 884 + K)
