@@ -1,7 +1,8 @@
-/* Host-side undefined-behaviour check of the oracle: built with -fsanitize=undefined
+/* Host-side sanitizer check of the oracle: built with -fsanitize=address,undefined
  * -fno-sanitize-recover by tests/test_oracle_sanitize.py together with oracle/dabnn_oracle.c and
- * run on small, awkward shapes (tails, borders wider than the image, strides above the pad).  It
- * exits 0 when no check fires; results are not compared here (the pins do that). */
+ * run on small, awkward shapes (tails, borders wider than the image, strides above the pad), every
+ * buffer allocated at exactly its size so that an access past either end is reported.  It exits 0
+ * when no check fires; results are not compared here (the pins do that). */
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -17,6 +18,15 @@ int oracle_bgemm(const float *A, const float *B, int32_t *C, int64_t M, int N, i
 int oracle_bn_sign_pack(const int32_t *y, const float *scale, const float *shift, const float *r,
                         float *x_out, uint64_t *bits, int64_t n_pixels, int C);
 int oracle_nhwc_to_nc1hwc2(const uint64_t *in, uint64_t *out, int N, int H, int W, int Cw);
+int oracle_bconv2d_at(const float *A, const float *Wt, const int32_t *idx, int64_t n_samples,
+                      int32_t *out, int N, int H, int W, int Cin, int Cout, int kh, int kw,
+                      int stride, int pad);
+int oracle_bconv2d_bnsign(const float *A, const float *Wt, const float *gamma, const float *beta,
+                          const float *mean, const float *var, float eps, uint64_t *out, int N,
+                          int H, int W, int Cin, int Cout, int kh, int kw, int stride, int pad);
+int oracle_glue(const float *x, const int32_t *y, const float *gamma, const float *beta,
+                float *x_next, int N, int H, int W, int Cin, int Ho, int Wo, int Cout, int K,
+                int stride);
 
 static float pm1(unsigned *st)
 {
@@ -50,12 +60,32 @@ int main(void)
         for (int c = 0; c < Cout; ++c) sc[c] = 0.01f * (float)(c - 1);
         if (oracle_bn_sign_pack(Y, sc, sc, z, z, ob, ny / Cout, Cout))
             return 3;
+        /* the last output, one by one; the fused batch-norm + sign; both into exact-size buffers */
+        int32_t idx[4] = {N - 1, Ho - 1, Wo - 1, Cout - 1}, one;
+        if (oracle_bconv2d_at(A, Wt, idx, 1, &one, N, H, W, Cin, Cout, k, k, s, p))
+            return 5;
+        if (oracle_bconv2d_bnsign(A, Wt, sc, sc, sc, sc, 1e-5f, ob, N, H, W, Cin, Cout, k, k, s, p))
+            return 6;
         free(A); free(Wt); free(Y); free(bits); free(sc); free(z); free(ob);
     }
     uint64_t in[2 * 3 * 3], out[2 * 2 * 3 * 2];
     for (int i = 0; i < 18; ++i) in[i] = (uint64_t)i * 0x9e3779b97f4a7c15ull;
     if (oracle_nhwc_to_nc1hwc2(in, out, 2, 1, 3, 3))
         return 4;
-    puts("oracle ubsan run ok");
+    /* the input generator of the full-network workload: stride 1 (identity shortcut) and stride 2
+     * (2x2 mean clipped at an odd edge, channels repeated) */
+    {
+        enum { N = 2, H = 5, W = 3, C = 3 };
+        float x[N * H * W * C], g[2 * C], b[2 * C];
+        int32_t y1[N * H * W * C], y2[N * 3 * 2 * 2 * C];
+        float o1[N * H * W * C], o2[N * 3 * 2 * 2 * C];
+        for (int i = 0; i < N * H * W * C; ++i) { x[i] = pm1(&st); y1[i] = i - 40; }
+        for (int i = 0; i < N * 3 * 2 * 2 * C; ++i) y2[i] = 7 - i;
+        for (int i = 0; i < 2 * C; ++i) { g[i] = 1.0f + i; b[i] = -0.5f * i; }
+        if (oracle_glue(x, y1, g, b, o1, N, H, W, C, H, W, C, 27, 1) ||
+            oracle_glue(x, y2, g, b, o2, N, H, W, C, 3, 2, 2 * C, 27, 2))
+            return 7;
+    }
+    puts("oracle sanitizer run ok");
     return 0;
 }

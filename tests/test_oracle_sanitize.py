@@ -1,5 +1,6 @@
-"""Host-only: the oracle under the undefined-behaviour sanitizer (signed overflow, shifts, bounds
-of fixed arrays, misaligned access, float-to-int range) on small awkward shapes."""
+"""Host-only: the oracle and the library's host dispatch code under the address and
+undefined-behaviour sanitizers (heap and stack bounds, use after free, signed overflow, shifts,
+misaligned access, float-to-int range) on small awkward shapes.  Nothing here touches a GPU."""
 import os
 import subprocess
 import sys
@@ -7,16 +8,55 @@ import sys
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_oracle_is_clean_under_ubsan(tmp_path):
-    exe = str(tmp_path / "oracle_ubsan")
-    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fsanitize=undefined",
-           "-fno-sanitize-recover=all", os.path.join(ROOT, "oracle", "dabnn_oracle.c"),
-           os.path.join(ROOT, "tests", "host", "oracle_ubsan_main.c"), "-o", exe, "-lm"]
+def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
+    exe = str(tmp_path / "oracle_sanitize")
+    # the sanitizer runtime is linked statically: it must not depend on its place in the
+    # loader's list of preloaded libraries
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", os.path.join(ROOT, "oracle", "dabnn_oracle.c"),
+           os.path.join(ROOT, "tests", "host", "oracle_sanitize_main.c"), "-o", exe, "-lm"]
     subprocess.run(cmd, check=True)
     out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     sys.stdout.write(out.stdout)
     sys.stderr.write(out.stderr)
-    assert out.returncode == 0 and "oracle ubsan run ok" in out.stdout
+    assert out.returncode == 0 and "oracle sanitizer run ok" in out.stdout
+
+
+def _library_objects():
+    import glob
+    import pytest
+    build_dir = os.path.join(ROOT, "paper_1908_05858_amd", "_build")
+    objs = [o for o in glob.glob(os.path.join(build_dir, "*.o")) if not o.endswith("dabnn_api.o")]
+    if len(objs) < 5:
+        pytest.skip("the library's object files are not in the tree (run build() first)")
+    return objs
+
+
+def test_host_dispatch_is_clean_under_asan_and_ubsan(tmp_path):
+    """csrc/dabnn_api.hip rebuilt with both sanitizers on the HOST side only, linked with the
+    library's other objects and a C++ driver (tests/host/dispatch_sanitize_main.cpp) into one
+    executable with the static sanitizer runtime, and run without a GPU."""
+    objs = _library_objects()
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    clangxx = "/opt/rocm/lib/llvm/bin/clang++"
+    if not os.path.exists(clangxx):
+        import pytest
+        pytest.skip("no clang++ next to hipcc")
+    api_o, drv_o, exe = (str(tmp_path / n) for n in ("api.o", "driver.o", "dispatch_sanitize"))
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
+    flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
+             "-packed-fp32-ops"] + [x for f in san for x in ("-Xarch_host", f)]
+    subprocess.run([hipcc] + flags + ["-c", os.path.join(ROOT, "paper_1908_05858_amd", "csrc", "dabnn_api.hip"),
+                                      "-o", api_o], check=True, capture_output=True)
+    subprocess.run([clangxx] + san + ["-O1", "-g", "-std=c++17", "-c",
+                                      os.path.join(ROOT, "tests", "host", "dispatch_sanitize_main.cpp"), "-o", drv_o],
+                   check=True, capture_output=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", drv_o, api_o]
+                   + objs + ["-o", exe], check=True, capture_output=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    sys.stdout.write(out.stdout)
+    sys.stderr.write(out.stderr[-2000:])
+    assert out.returncode == 0 and "host dispatch sanitizer run ok" in out.stdout
 
 
 def test_host_dispatch_is_clean_under_ubsan(tmp_path):
@@ -24,11 +64,7 @@ def test_host_dispatch_is_clean_under_ubsan(tmp_path):
     rebuilt with the undefined-behaviour sanitizer on the HOST side only and driven through the
     C ABI without a GPU: every call here must be refused or computed on the host."""
     import glob
-    build_dir = os.path.join(ROOT, "paper_1908_05858_amd", "_build")
-    objs = [o for o in glob.glob(os.path.join(build_dir, "*.o")) if not o.endswith("dabnn_api.o")]
-    if len(objs) < 5:
-        import pytest
-        pytest.skip("the library's object files are not in the tree (run build() first)")
+    objs = _library_objects()
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     api_o = str(tmp_path / "dabnn_api_ubsan.o")
     lib = str(tmp_path / "libdabnn_ubsan.so")
