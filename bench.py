@@ -3,11 +3,22 @@
 Bi-Real-Net-18 body at 224x224 input, batch 256, each preceded by the bit-pack of its fp32
 activation.  One step = 16 x (dabnn_bitpack + dabnn_bconv2d) over inputs resident in HBM.
 
-Prints ONE JSON line.  `value` is binary-convolution GOPS (2*K*Cout*Ho*Wo*N summed over the 16
-layers, divided by the wall time of a whole step, bit-packing included).  After the headline
-region the same layers are timed through two widened entry points, reported beside it and never
-in it: `fused_bnsign` (conv + BN threshold + bit-pack in one kernel) and `int8_mfma_comparison`
-(bits expanded to +-1 bytes, int8 matrix cores).
+Prints ONE JSON line.
+
+  value            binary-convolution GOPS: 2*K*Cout*Ho*Wo*N summed over the 16 layers, divided by
+                   the wall time of a whole step (bit-packing included), from a loop of exactly
+                   --steps steps that carries no instrumentation.
+  roofline         from a separate SAMPLING PASS after the headline loop: every launch of a step
+                   is bracketed by HIP events on the launch stream, --samples times (default 24,
+                   whatever --steps is); per layer the median and the minimum are kept.
+                   achieved = sum of the layers' ops / sum of the layers' median intervals.
+  configs          the other four benchmark configurations (single 14x14x64 convolution, the
+                   stride-1 sweep at batch 1 and 64, the bit-pack shapes incl. C = 80 / 200, the
+                   stride-2 layers at batch 128): microseconds, GOPS or GB/s, roofline fraction
+                   and the oracle's time on the same tensors.  Never part of `value`.
+  fused_bnsign, bireal_block_chain, batch1_chain_latency, int8_mfma_comparison
+                   widened entry points on the same layers, timed after everything above.
+  cpu_baseline     the CPU oracle on the same 16 layers, all host threads.
 """
 import argparse
 import json
@@ -25,8 +36,9 @@ if ROOT not in sys.path:
 # 2 lane-ops => 32 ops per lane-op => 1258.29 TOP/s.
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 * 32 / 1e12
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per step (16 launches) at batch 256, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) scaled by a plain 1 GiB copy; see profiles/bench_bireal18_b256_hbm_traffic.md.
+INFINITY_CACHE_BYTES = 256e6
+# HBM bytes per step (16 launches each) at batch 256, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# then WRITE_SIZE) scaled by a plain 1 GiB copy; see profiles/bireal18_b256_hbm_traffic.md.
 # Algorithmic: conv 1.597e9 (56 MB read + 1541 MB written), bit-pack 1.775e9.
 MEASURED_TRAFFIC_B256 = {"bconv": 1.947e9, "bitpack": 1.776e9}
 
@@ -36,8 +48,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--samples", type=int, default=24,
+                    help="event-bracketed samples per launch in the sampling pass (roofline)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch (default 256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the other configs and the widened entry points (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device tensor copy (a kernel of known "
                          "HBM traffic) so that counter runs under rocprofv3 --pmc can be scaled")
@@ -58,6 +74,38 @@ def main():
     torch.cuda.set_device(0)
     N = args.batch or wl.CFG5_BATCH
     layers = wl.BIREAL18_BODY
+    want_oracle = not args.no_cpu_baseline
+    if want_oracle:
+        import oracle
+        oracle.build()
+
+    def event():
+        return torch.cuda.Event(enable_timing=True)
+
+    def launch_us(fn, reps=20, inner=1):
+        """Median and minimum, in microseconds per launch, of `reps` HIP-event intervals around
+        `inner` back-to-back calls of fn() on the launch stream."""
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(event(), event()) for _ in range(reps)]
+        for e0, e1 in evs:
+            e0.record()
+            for _ in range(inner):
+                fn()
+            e1.record()
+        torch.cuda.synchronize()
+        us = sorted(e0.elapsed_time(e1) * 1e3 / inner for e0, e1 in evs)
+        return us[len(us) // 2], us[0]
+
+    def wall_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
 
     # ---- inputs: seeded, synthetic, resident in HBM before any timing ---------------------
     xs, wps, acts, ys = [], [], [], []
@@ -70,18 +118,11 @@ def main():
         ys.append(torch.empty((N, L.Ho, L.Wo, L.Cout), dtype=torch.int32, device="cuda"))
     torch.cuda.synchronize()
 
-    def step(events=None, probe=-1):
-        """One pass of the hot path.  With `events`, layer `probe` of this step is bracketed by
-        three HIP events on the launch stream (before bit-pack, between, after the conv)."""
+    def step():
+        """One pass of the hot path."""
         for li, L in enumerate(layers):
-            if li == probe:
-                events[0].record()
             binding.bitpack(xs[li], out=acts[li])
-            if li == probe:
-                events[1].record()
             binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li])
-            if li == probe:
-                events[2].record()
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
@@ -94,206 +135,49 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps.  Step k carries HIP events (on the stream the kernels
-    # are launched on) around layer k mod 16 only, so every kernel launch of the step is sampled
-    # K/16 times while the instrumentation stays at three events per step.
-    all_events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
+    # ---- headline: exactly K steps, nothing but the 32 launches of each step ---------------
     t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(all_events[k], k % len(layers))
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    pack_ms = np.zeros(len(layers))
-    conv_ms = np.zeros(len(layers))
-    samples = np.zeros(len(layers))
-    for k, ev in enumerate(all_events):
-        li = k % len(layers)
-        pack_ms[li] += ev[0].elapsed_time(ev[1])
-        conv_ms[li] += ev[1].elapsed_time(ev[2])
-        samples[li] += 1
-    if samples.min() == 0:
-        print("bench.py: --steps must be at least 16 so that every layer is sampled", file=sys.stderr)
-        sys.exit(2)
-    pack_ms /= samples
-    conv_ms /= samples
-
-    # the same K steps once more without the events, to show what the instrumentation costs
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for k in range(args.steps):
+    for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    ms_plain = (time.perf_counter() - t2) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # Widened row: the same 16 convolutions with the batch-norm threshold and the bit-pack of the
-    # result fused into the kernel (dabnn_bconv2d_bnsign): packed words in, packed words out, no
-    # int32 tensor and no separate bit-pack launch.  Reported beside the headline, never in it.
-    rng = np.random.default_rng(wl.seed_for(5, 999))
-    fused_args = []
-    for li, L in enumerate(layers):
-        if L.Cout % 64:
-            fused_args = None
-            break
-        thr, flip = binding.bn_thresholds(rng.uniform(0.5, 1.5, L.Cout), rng.normal(0, 0.3, L.Cout),
-                                          rng.normal(0, 5, L.Cout), rng.uniform(1, 30, L.Cout),
-                                          1e-5, L.K)
-        out = torch.empty((N, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda")
-        fused_args.append((thr, flip, out))
-    fused_ms = None
-    if fused_args:
-        def fused_step():
-            for li, L in enumerate(layers):
-                thr, flip, out = fused_args[li]
-                binding.bconv2d_bnsign(acts[li], wps[li], thr, flip, L.Cin, L.stride, 1, out=out)
-        fused_step()
-        torch.cuda.synchronize()
-        t3 = time.perf_counter()
-        for k in range(args.steps):
-            fused_step()
-        torch.cuda.synchronize()
-        fused_ms = (time.perf_counter() - t3) * 1e3 / args.steps
-
-    # Comparison row: the same convolutions on the int8 matrix cores with every bit expanded to a
-    # +-1 byte (dabnn_expand_int8 + dabnn_bconv2d_int8).  One step = 16 x (expand the packed
-    # activations, convolve); filters are expanded ahead of time like they are packed ahead of time.
-    mfma_ms = mfma_conv_ms = None
-    if all(L.Cin % 64 == 0 and L.Cout % 64 == 0 for L in layers):
-        w8s = [binding.expand_int8(wps[li], L.Cin) for li, L in enumerate(layers)]
-        a8s = [torch.empty((N, L.H, L.W, L.Cin), dtype=torch.int8, device="cuda") for L in layers]
-
-        def mfma_step(expand=True):
-            for li, L in enumerate(layers):
-                if expand:
-                    binding.expand_int8(acts[li], L.Cin, out=a8s[li])
-                binding.bconv2d_int8(a8s[li], w8s[li], L.stride, 1, out=ys[li])
-        mfma_step()
-        torch.cuda.synchronize()
-        k_cmp = max(4, args.steps // 4)
-        t4 = time.perf_counter()
-        for k in range(k_cmp):
-            mfma_step()
-        torch.cuda.synchronize()
-        mfma_ms = (time.perf_counter() - t4) * 1e3 / k_cmp
-        t5 = time.perf_counter()
-        for k in range(k_cmp):
-            mfma_step(expand=False)
-        torch.cuda.synchronize()
-        mfma_conv_ms = (time.perf_counter() - t5) * 1e3 / k_cmp
-        del w8s, a8s
-
-    # The same body with its real data dependencies (Sec. 2.3's network): each convolution reads
-    # the bits the previous block produced, and dabnn_bn_sign_pack turns its int32 output, plus the
-    # real-valued shortcut, into the next block's bits and shortcut.  Where the shape changes
-    # (stride 2) a resident synthetic tensor stands in for the float downsampling shortcut.
-    chain_ms = None
-    if all(L.Cout % 64 == 0 for L in layers):
-        scales = [torch.full((L.Cout,), 1.0 / (L.K ** 0.5), dtype=torch.float32, device="cuda") for L in layers]
-        shifts = [torch.from_numpy(wl.affine(L.Cout, wl.seed_for(5, 200 + li))[1]).cuda() for li, L in enumerate(layers)]
-        zs = [torch.empty((N, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
-        bits_out = [torch.empty((N, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
-        down = {li: torch.randn((N, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
-                if li == 0 or L.stride != 1}
-
-        def chain_step(fused):
-            a_in = acts[0]
-            for li, L in enumerate(layers):
-                r = down[li] if li in down else zs[li - 1]
-                if fused:
-                    binding.bconv2d_bn_residual(a_in, wps[li], scales[li], shifts[li], r, L.Cin, L.stride, 1,
-                                                x_out=zs[li], out=bits_out[li])
-                else:
-                    binding.bconv2d(a_in, wps[li], L.Cin, L.stride, 1, out=ys[li])
-                    binding.bn_sign_pack(ys[li], scales[li], shifts[li], r, x_out=zs[li], out=bits_out[li])
-                a_in = bits_out[li]
-        k_chain = max(4, args.steps // 4)
-        chain_ms = []
-        for fused in (False, True):
-            chain_step(fused)
-            torch.cuda.synchronize()
-            t6 = time.perf_counter()
-            for k in range(k_chain):
-                chain_step(fused)
-            torch.cuda.synchronize()
-            chain_ms.append((time.perf_counter() - t6) * 1e3 / k_chain)
-        del zs, bits_out, down
-
-    # Batch-1 latency of the dependent 16-block chain (the paper's deployment case is one image
-    # at a time): launch-bound, so it is also replayed from a HIP graph.
-    lat = None
-    if all(L.Cout % 64 == 0 for L in layers):
-        a1 = torch.zeros((1, layers[0].H, layers[0].W, layers[0].Cin // 64), dtype=torch.int64, device="cuda")
-        z1 = [torch.empty((1, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
-        b1 = [torch.empty((1, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
-        d1 = {li: torch.randn((1, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
-              if li == 0 or L.stride != 1}
-        sc1 = [torch.full((L.Cout,), 1.0 / (L.K ** 0.5), dtype=torch.float32, device="cuda") for L in layers]
-        sh1 = [torch.zeros((L.Cout,), dtype=torch.float32, device="cuda") for L in layers]
-
-        def one_image():
-            a_in = a1
-            for li, L in enumerate(layers):
-                r = d1[li] if li in d1 else z1[li - 1]
-                binding.bconv2d_bn_residual(a_in, wps[li], sc1[li], sh1[li], r, L.Cin, L.stride, 1,
-                                            x_out=z1[li], out=b1[li])
-                a_in = b1[li]
-
-        def wall_us(f, reps=200):
-            f()
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for _ in range(reps):
-                f()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t) * 1e6 / reps
-        eager_us = wall_us(one_image)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            one_image()
-        lat = {"what": "16 dependent blocks (dabnn_bconv2d_bn_residual) on one 224x224 image's feature maps",
-               "eager_us": round(eager_us, 1), "hip_graph_replay_us": round(wall_us(graph.replay), 1)}
-        del graph
-
-    # The largest bit-pack shape of the parity configs (benchmark configs[2]: 256x56x56x256,
-    # 822 MB of fp32), far beyond the 256 MB Infinity Cache: the launch the HBM fraction of the
-    # bit-pack kernel is claimed on.  One HIP-event pair per launch.
-    big = None
-    if N == wl.CFG5_BATCH:
-        shape = wl.CFG3_SHAPES[2]
-        xb = torch.empty(shape, dtype=torch.float32, device="cuda").normal_()
-        ob = torch.empty(shape[:-1] + ((shape[-1] + 63) // 64,), dtype=torch.int64, device="cuda")
-        binding.bitpack(xb, out=ob)
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-        for e0, e1 in evs:
-            e0.record()
-            binding.bitpack(xb, out=ob)
-            e1.record()
-        torch.cuda.synchronize()
-        us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
-        moved = xb.numel() * 4 + ob.numel() * 8
-        big = {"shape": "x".join(map(str, shape)), "MB_moved": round(moved / 1e6, 1),
-               "median_us": round(us[len(us) // 2], 2), "min_us": round(us[0], 2),
-               "GBps_median": round(moved / us[len(us) // 2] / 1e3, 1),
-               "frac_of_hbm_peak": round(moved / us[len(us) // 2] / 1e3 / HBM_PEAK_GBPS, 4)}
-        del xb, ob
+    # ---- sampling pass: every launch of a step between HIP events, `samples` times ---------
+    # The events sit on the stream the kernels are launched on.  An interval holds one kernel
+    # plus the gap the command processor leaves between two dependent dispatches (about 3 us).
+    S = max(1, args.samples)
+    ev = [[[event() for _ in range(3)] for _ in layers] for _ in range(S)]
+    torch.cuda.synchronize()
+    for s in range(S):
+        for li, L in enumerate(layers):
+            ev[s][li][0].record()
+            binding.bitpack(xs[li], out=acts[li])
+            ev[s][li][1].record()
+            binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li])
+            ev[s][li][2].record()
+    torch.cuda.synchronize()
+    pack_us = np.array([[ev[s][li][0].elapsed_time(ev[s][li][1]) * 1e3 for li in range(len(layers))]
+                        for s in range(S)])
+    conv_us = np.array([[ev[s][li][1].elapsed_time(ev[s][li][2]) * 1e3 for li in range(len(layers))]
+                        for s in range(S)])
+    del ev
+    pack_med, pack_min = np.median(pack_us, axis=0), pack_us.min(axis=0)
+    conv_med, conv_min = np.median(conv_us, axis=0), conv_us.min(axis=0)
 
     ops = [L.ops(N) for L in layers]
     total_ops = float(sum(ops))
     pack_bytes = [xs[li].numel() * 4 + acts[li].numel() * 8 for li in range(len(layers))]
-    conv_tops = total_ops / (conv_ms.sum() * 1e-3) / 1e12       # conv kernels only
-    pack_gbps = sum(pack_bytes) / (pack_ms.sum() * 1e-3) / 1e9  # bit-pack kernels only
-
+    conv_tops = total_ops / (conv_med.sum() * 1e-6) / 1e12       # conv launches only
+    pack_gbps = sum(pack_bytes) / (pack_med.sum() * 1e-6) / 1e9  # bit-pack launches only
     per_layer = []
     for li, L in enumerate(layers):
         per_layer.append({
             "layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}",
-            "bconv_us": round(conv_ms[li] * 1e3, 2),
-            "bconv_TOPs": round(ops[li] / (conv_ms[li] * 1e-3) / 1e12, 1),
-            "bitpack_us": round(pack_ms[li] * 1e3, 2),
-            "bitpack_GBps": round(pack_bytes[li] / (pack_ms[li] * 1e-3) / 1e9, 1),
+            "bconv_us_median": round(float(conv_med[li]), 2), "bconv_us_min": round(float(conv_min[li]), 2),
+            "bconv_TOPs": round(ops[li] / (conv_med[li] * 1e-6) / 1e12, 1),
+            "bconv_frac_of_valu_peak": round(ops[li] / (conv_med[li] * 1e-6) / 1e12 / VALU_PEAK_TOPS, 4),
+            "bitpack_us_median": round(float(pack_med[li]), 2), "bitpack_us_min": round(float(pack_min[li]), 2),
+            "bitpack_GBps": round(pack_bytes[li] / (pack_med[li] * 1e-6) / 1e9, 1),
         })
 
     result = {
@@ -316,8 +200,7 @@ def main():
             "layers": len(layers),
             "binary_ops_per_step": total_ops,
         },
-        "ms_per_step_without_events": round(ms_plain, 4),
-        "event_samples_per_layer": int(samples.min()),
+        "event_samples_per_layer": S,
         "bconv_only_GOPS": round(conv_tops * 1e3, 1),
         "bconv_frac_of_valu_peak": round(conv_tops / VALU_PEAK_TOPS, 4),
         "bitpack_GBps": round(pack_gbps, 1),
@@ -329,6 +212,8 @@ def main():
             "peak": round(VALU_PEAK_TOPS, 2),
             "unit": "TOP/s",
             "frac": round(conv_tops / VALU_PEAK_TOPS, 4),
+            "frac_from_minimum_intervals": round(total_ops / (conv_min.sum() * 1e-6) / 1e12 / VALU_PEAK_TOPS, 4),
+            "samples_per_launch": S,
             "traffic": MEASURED_TRAFFIC_B256["bconv"] if N == 256 else None,
             "traffic_note": "HBM bytes per step over the 16 conv launches (algorithmic 1.597e9)",
         },
@@ -339,48 +224,34 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(pack_gbps / HBM_PEAK_GBPS, 4),
+            "samples_per_launch": S,
             "traffic": MEASURED_TRAFFIC_B256["bitpack"] if N == 256 else None,
             "traffic_note": "HBM bytes per step over the 16 bit-pack launches (algorithmic 1.775e9)",
         },
         "per_layer": per_layer,
     }
-    if chain_ms is not None:
-        result["bireal_block_chain"] = {
-            "what": "16 dependent blocks: binary conv on the previous block's bits, then BN + real-valued "
-                    "shortcut + sign + bit-pack producing the next block's bits and shortcut; as two "
-                    "calls per block (dabnn_bconv2d, dabnn_bn_sign_pack) and as one "
-                    "(dabnn_bconv2d_bn_residual)",
-            "two_calls_per_block_ms_per_step": round(chain_ms[0], 4),
-            "two_calls_per_block_GOPS": round(total_ops / (chain_ms[0] * 1e-3) / 1e9, 1),
-            "one_call_per_block_ms_per_step": round(chain_ms[1], 4),   # dabnn_bconv2d_bn_residual
-            "one_call_per_block_GOPS": round(total_ops / (chain_ms[1] * 1e-3) / 1e9, 1),
-        }
-    if lat is not None:
-        result["batch1_chain_latency"] = lat
-    if big is not None:
-        result["roofline_bitpack"]["largest_launch"] = big
-    if mfma_ms is not None:
-        result["int8_mfma_comparison"] = {
-            "what": "16 x (dabnn_expand_int8 of the packed activations + dabnn_bconv2d_int8 on "
-                    "v_mfma_i32_32x32x32_i8), same outputs; comparison only, not the method's path",
-            "ms_per_step": round(mfma_ms, 4),
-            "GOPS": round(total_ops / (mfma_ms * 1e-3) / 1e9, 1),
-            "conv_only_ms_per_step": round(mfma_conv_ms, 4),
-            "conv_only_GOPS": round(total_ops / (mfma_conv_ms * 1e-3) / 1e9, 1),
-            "conv_only_frac_of_int8_mfma_peak": round(total_ops / (mfma_conv_ms * 1e-3) / 5.0e15, 4),
-        }
-    if fused_ms is not None:
-        result["fused_bnsign"] = {
-            "what": "16 x dabnn_bconv2d_bnsign (conv + BN threshold + bit-pack of the result in one "
-                    "kernel), packed input resident",
-            "ms_per_step": round(fused_ms, 4),
-            "GOPS": round(total_ops / (fused_ms * 1e-3) / 1e9, 1),
-            "frac_of_valu_peak": round(total_ops / (fused_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, 4),
-        }
+
+    # The largest bit-pack shape of the parity configs (256x56x56x256, 822 MB of fp32), far beyond
+    # the 256 MB Infinity Cache: the launch the HBM fraction of the bit-pack kernel is claimed on.
+    if N == wl.CFG5_BATCH:
+        shape = wl.CFG3_SHAPES[2]
+        xb = torch.empty(shape, dtype=torch.float32, device="cuda").normal_()
+        ob = torch.empty(shape[:-1] + ((shape[-1] + 63) // 64,), dtype=torch.int64, device="cuda")
+        med, mn = launch_us(lambda: binding.bitpack(xb, out=ob), reps=max(10, S))
+        moved = xb.numel() * 4 + ob.numel() * 8
+        result["roofline_bitpack"]["largest_launch"] = {
+            "shape": "x".join(map(str, shape)), "MB_moved": round(moved / 1e6, 1),
+            "median_us": round(med, 2), "min_us": round(mn, 2),
+            "GBps_median": round(moved / med / 1e3, 1),
+            "frac_of_hbm_peak": round(moved / med / 1e3 / HBM_PEAK_GBPS, 4)}
+        del xb, ob
+
+    if not args.headline_only:
+        result["configs"] = other_configs(binding, wl, np, torch, launch_us, want_oracle)
+        widened_rows(result, args, binding, wl, np, torch, layers, N, acts, wps, ys, total_ops, wall_ms)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
-    if not args.no_cpu_baseline:
-        import oracle
+    if want_oracle:
         n_img = N
         cpu_x = [x.cpu().numpy() for x in xs]
         cpu_w = [wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li)) for li, L in enumerate(layers)]
@@ -405,6 +276,196 @@ def main():
         }
 
     print(json.dumps(result))
+
+
+def other_configs(binding, wl, np, torch, launch_us, want_oracle):
+    """BASELINE.json configs[0..3]: per launch microseconds (median of 20 HIP-event intervals;
+    launches below 20 us are timed 20 at a time between one event pair), throughput, roofline
+    fraction, and the oracle's wall time for the same tensors on the host."""
+    if want_oracle:
+        import oracle
+    out = {}
+
+    def conv_row(L, n, seed, p_plus=0.5):
+        x = wl.activations((n, L.H, L.W, L.Cin), seed)
+        wf = wl.weights((L.Cout, 3, 3, L.Cin), seed + 1, p_plus)
+        xg = torch.from_numpy(x).cuda()
+        wp = binding.pack_weights(torch.from_numpy(wf).cuda())
+        a = binding.bitpack(xg)
+        y = torch.empty((n, L.Ho, L.Wo, L.Cout), dtype=torch.int32, device="cuda")
+        conv = lambda: binding.bconv2d(a, wp, L.Cin, L.stride, 1, out=y)
+        pack = lambda: binding.bitpack(xg, out=a)
+        med, _ = launch_us(conv)
+        if med < 20.0:
+            med, _ = launch_us(conv, inner=20)
+        pmed, _ = launch_us(pack)
+        if pmed < 20.0:
+            pmed, _ = launch_us(pack, inner=20)
+        ops = L.ops(n)
+        moved = x.size * 4 + a.numel() * 8
+        row = {"layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}", "batch": n,
+               "bconv_us": round(med, 2), "bconv_GOPS": round(ops / med / 1e3, 1),
+               "bconv_frac_of_valu_peak": round(ops / med / 1e6 / VALU_PEAK_TOPS, 4),
+               "bitpack_us": round(pmed, 2), "bitpack_GBps": round(moved / pmed / 1e3, 1)}
+        # fewer outputs than the chip has lanes in flight: the launch is latency-bound
+        if n * L.Ho * L.Wo * L.Cout < 256 * 4 * 64 * 16:
+            row["note"] = "latency-bound: fewer outputs than resident lanes x 16 channels"
+        if want_oracle:
+            t = time.perf_counter()
+            oracle.bconv2d(x, wf, L.stride, 1)
+            dt = time.perf_counter() - t
+            row["oracle_ms"] = round(dt * 1e3, 2)
+            row["oracle_GOPS"] = round(ops / dt / 1e9, 1)
+        return row
+
+    out["cfg1_single_conv"] = conv_row(wl.CFG1_LAYER, 1, wl.seed_for(1))
+    out["cfg2_stride1_sweep"] = [conv_row(L, n, wl.seed_for(2, li))
+                                 for li, L in enumerate(wl.CFG2_LAYERS) for n in wl.CFG2_BATCHES]
+    out["cfg4_stride2_batch128"] = [conv_row(L, wl.CFG4_BATCH, wl.seed_for(4, li), wl.CFG4_P_PLUS)
+                                    for li, L in enumerate(wl.CFG4_LAYERS)]
+    rows = []
+    for shape in wl.CFG3_SHAPES:
+        x = wl.inject_zeros(wl.activations(shape, wl.seed_for(3, shape[-1] + shape[0])), wl.seed_for(3, 1))
+        xg = torch.from_numpy(x).cuda()
+        o = torch.empty(shape[:-1] + ((shape[-1] + 63) // 64,), dtype=torch.int64, device="cuda")
+        f = lambda: binding.bitpack(xg, out=o)
+        med, _ = launch_us(f)
+        if med < 20.0:
+            med, _ = launch_us(f, inner=20)
+        moved = x.size * 4 + o.numel() * 8
+        row = {"shape": "x".join(map(str, shape)), "MB_moved": round(moved / 1e6, 3), "us": round(med, 2),
+               "GBps": round(moved / med / 1e3, 1),
+               "frac_of_hbm_peak": round(moved / med / 1e3 / HBM_PEAK_GBPS, 4)}
+        if moved < INFINITY_CACHE_BYTES:
+            row["note"] = ("launch-bound" if med < 10.0 else "cache-resident") + \
+                          ": the tensor fits the 256 MB Infinity Cache, not an HBM figure"
+        if want_oracle:
+            t = time.perf_counter()
+            oracle.bitpack(x)
+            dt = time.perf_counter() - t
+            row["oracle_ms"] = round(dt * 1e3, 3)
+            row["oracle_GBps"] = round(moved / dt / 1e9, 2)
+        rows.append(row)
+        del xg, o
+    out["cfg3_bitpack"] = rows
+    return out
+
+
+def widened_rows(result, args, binding, wl, np, torch, layers, N, acts, wps, ys, total_ops, wall_ms):
+    """Widened entry points on the same 16 layers; reported beside the headline, never in it."""
+    reps = max(4, args.steps // 4)
+    # conv + BN threshold + bit-pack of the result in one kernel: packed words in, packed words out
+    if all(L.Cout % 64 == 0 for L in layers):
+        rng = np.random.default_rng(wl.seed_for(5, 999))
+        fused_args = []
+        for li, L in enumerate(layers):
+            thr, flip = binding.bn_thresholds(rng.uniform(0.5, 1.5, L.Cout), rng.normal(0, 0.3, L.Cout),
+                                              rng.normal(0, 5, L.Cout), rng.uniform(1, 30, L.Cout),
+                                              1e-5, L.K)
+            out = torch.empty((N, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda")
+            fused_args.append((thr, flip, out))
+
+        def fused_step():
+            for li, L in enumerate(layers):
+                thr, flip, out = fused_args[li]
+                binding.bconv2d_bnsign(acts[li], wps[li], thr, flip, L.Cin, L.stride, 1, out=out)
+        fused_ms = wall_ms(fused_step, reps)
+        result["fused_bnsign"] = {
+            "what": "16 x dabnn_bconv2d_bnsign (conv + BN threshold + bit-pack of the result in one "
+                    "kernel), packed input resident",
+            "ms_per_step": round(fused_ms, 4),
+            "GOPS": round(total_ops / (fused_ms * 1e-3) / 1e9, 1),
+            "frac_of_valu_peak": round(total_ops / (fused_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, 4),
+        }
+        del fused_args
+
+        # The body with its real data dependencies (Sec. 2.3's network): each convolution reads the
+        # bits the previous block produced, and the BN + shortcut + sign + pack layer turns its
+        # output, plus the real-valued shortcut, into the next block's bits and shortcut.  Where
+        # the shape changes (stride 2) a resident synthetic tensor stands in for the float
+        # downsampling shortcut.
+        scales = [torch.full((L.Cout,), 1.0 / (L.K ** 0.5), dtype=torch.float32, device="cuda") for L in layers]
+        shifts = [torch.from_numpy(wl.affine(L.Cout, wl.seed_for(5, 200 + li))[1]).cuda() for li, L in enumerate(layers)]
+        zs = [torch.empty((N, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
+        bits_out = [torch.empty((N, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
+        down = {li: torch.randn((N, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
+                if li == 0 or L.stride != 1}
+
+        def chain_step(fused):
+            a_in = acts[0]
+            for li, L in enumerate(layers):
+                r = down[li] if li in down else zs[li - 1]
+                if fused:
+                    binding.bconv2d_bn_residual(a_in, wps[li], scales[li], shifts[li], r, L.Cin, L.stride, 1,
+                                                x_out=zs[li], out=bits_out[li])
+                else:
+                    binding.bconv2d(a_in, wps[li], L.Cin, L.stride, 1, out=ys[li])
+                    binding.bn_sign_pack(ys[li], scales[li], shifts[li], r, x_out=zs[li], out=bits_out[li])
+                a_in = bits_out[li]
+        chain_ms = [wall_ms(lambda: chain_step(f), reps) for f in (False, True)]
+        result["bireal_block_chain"] = {
+            "what": "16 dependent blocks: binary conv on the previous block's bits, then BN + real-valued "
+                    "shortcut + sign + bit-pack producing the next block's bits and shortcut; as two "
+                    "calls per block (dabnn_bconv2d, dabnn_bn_sign_pack) and as one "
+                    "(dabnn_bconv2d_bn_residual)",
+            "two_calls_per_block_ms_per_step": round(chain_ms[0], 4),
+            "two_calls_per_block_GOPS": round(total_ops / (chain_ms[0] * 1e-3) / 1e9, 1),
+            "one_call_per_block_ms_per_step": round(chain_ms[1], 4),
+            "one_call_per_block_GOPS": round(total_ops / (chain_ms[1] * 1e-3) / 1e9, 1),
+        }
+        del zs, bits_out, down
+
+        # Batch-1 latency of the dependent 16-block chain (the paper's deployment case is one image
+        # at a time): launch-bound, so it is also replayed from a HIP graph.
+        a1 = torch.zeros((1, layers[0].H, layers[0].W, layers[0].Cin // 64), dtype=torch.int64, device="cuda")
+        z1 = [torch.empty((1, L.Ho, L.Wo, L.Cout), dtype=torch.float32, device="cuda") for L in layers]
+        b1 = [torch.empty((1, L.Ho, L.Wo, L.Cout // 64), dtype=torch.int64, device="cuda") for L in layers]
+        d1 = {li: torch.randn((1, L.Ho, L.Wo, L.Cout), device="cuda") for li, L in enumerate(layers)
+              if li == 0 or L.stride != 1}
+        sh1 = [torch.zeros((L.Cout,), dtype=torch.float32, device="cuda") for L in layers]
+
+        def one_image():
+            a_in = a1
+            for li, L in enumerate(layers):
+                r = d1[li] if li in d1 else z1[li - 1]
+                binding.bconv2d_bn_residual(a_in, wps[li], scales[li], sh1[li], r, L.Cin, L.stride, 1,
+                                            x_out=z1[li], out=b1[li])
+                a_in = b1[li]
+        eager_us = wall_ms(one_image, 200) * 1e3
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_image()
+        result["batch1_chain_latency"] = {
+            "what": "16 dependent blocks (dabnn_bconv2d_bn_residual) on one 224x224 image's feature maps",
+            "eager_us": round(eager_us, 1), "hip_graph_replay_us": round(wall_ms(graph.replay, 200) * 1e3, 1)}
+        del graph
+
+    # Comparison row: the same convolutions on the int8 matrix cores with every bit expanded to a
+    # +-1 byte (dabnn_expand_int8 + dabnn_bconv2d_int8).  One step = 16 x (expand the packed
+    # activations, convolve); filters are expanded ahead of time like they are packed ahead of time.
+    if all(L.Cin % 64 == 0 and L.Cout % 64 == 0 for L in layers):
+        w8s = [binding.expand_int8(wps[li], L.Cin) for li, L in enumerate(layers)]
+        a8s = [torch.empty((N, L.H, L.W, L.Cin), dtype=torch.int8, device="cuda") for L in layers]
+
+        def mfma_step(expand=True):
+            for li, L in enumerate(layers):
+                if expand:
+                    binding.expand_int8(acts[li], L.Cin, out=a8s[li])
+                binding.bconv2d_int8(a8s[li], w8s[li], L.stride, 1, out=ys[li])
+        mfma_ms = wall_ms(mfma_step, reps)
+        mfma_conv_ms = wall_ms(lambda: mfma_step(expand=False), reps)
+        result["int8_mfma_comparison"] = {
+            "what": "16 x (dabnn_expand_int8 of the packed activations + dabnn_bconv2d_int8 on "
+                    "v_mfma_i32_32x32x32_i8), same outputs.  A measured data point of an UNTUNED "
+                    "implicit GEMM (LDS-bandwidth-bound 64x64 wavefront tiles), not a verdict on "
+                    "the matrix-core route",
+            "ms_per_step": round(mfma_ms, 4),
+            "GOPS": round(total_ops / (mfma_ms * 1e-3) / 1e9, 1),
+            "conv_only_ms_per_step": round(mfma_conv_ms, 4),
+            "conv_only_GOPS": round(total_ops / (mfma_conv_ms * 1e-3) / 1e9, 1),
+            "conv_only_frac_of_int8_mfma_peak": round(total_ops / (mfma_conv_ms * 1e-3) / 5.0e15, 4),
+        }
+        del w8s, a8s
 
 
 if __name__ == "__main__":

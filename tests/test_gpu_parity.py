@@ -48,8 +48,6 @@ def words(t):
 @pytest.mark.parametrize("shape", wl.CFG3_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("mode", [0, 1])
 def test_bitpack_cfg3(dabnn, oracle, shape, mode):
-    if mode == 1 and np.prod(shape) > 5e7:
-        pytest.skip("largest tensor is covered with the default sign rule")
     print("bitpack", shape, "mode", mode, flush=True)
     x = wl.inject_zeros(wl.activations(shape, wl.seed_for(3, shape[-1] + shape[0])), wl.seed_for(3, 1))
     got = words(dabnn.bitpack(gpu(x), sign_mode=mode))
@@ -200,8 +198,8 @@ def test_bconv2d_bn_residual_sixteen_channel_groups_forced(dabnn, oracle, option
 
 
 def test_bconv2d_bn_residual_full_batch_layer(dabnn, oracle):
-    """Batch 256 at a benchmark shape: sampled pixels (all channels) against the oracle chain, and
-    the whole result against the library's own two-call sequence."""
+    """Batch 256 at a benchmark shape: every z (bit for bit) and every packed word against the
+    oracle chain, and the whole result against the library's own two-call sequence."""
     L = wl.BIREAL18_BODY[5]
     N = wl.CFG5_BATCH
     x = wl.activations((N, L.H, L.W, L.Cin), wl.seed_for(5, 105))
@@ -215,11 +213,9 @@ def test_bconv2d_bn_residual_full_batch_layer(dabnn, oracle):
     z, bits = dabnn.bconv2d_bn_residual(a, wp, sg, hg, rg, L.Cin, L.stride, 1)
     z2, bits2 = dabnn.bn_sign_pack(dabnn.bconv2d(a, wp, L.Cin, L.stride, 1), sg, hg, rg)
     assert torch.equal(z.view(torch.int32), z2.view(torch.int32)) and torch.equal(bits, bits2)
-    for n in (0, N // 2, N - 1):
-        oy = oracle.bconv2d(x[n:n + 1], wf, L.stride, 1)
-        oz, ob = oracle.bn_sign_pack(oy, scale, shift, r[n:n + 1])
-        assert np.array_equal(z[n:n + 1].cpu().numpy().view(np.uint32), oz.view(np.uint32))
-        assert np.array_equal(words(bits[n:n + 1]), ob)
+    oz, ob = oracle.bn_sign_pack(oracle.bconv2d(x, wf, L.stride, 1), scale, shift, r)
+    assert np.array_equal(z.cpu().numpy().view(np.uint32), oz.view(np.uint32))
+    assert np.array_equal(words(bits), ob)
 
 
 def test_bireal_block_chain(dabnn, oracle):
@@ -400,8 +396,8 @@ def test_bconv2d_zeropad(dabnn, oracle, shape):
 
 
 def test_bconv2d_zeropad_full_batch_layer(dabnn, oracle):
-    """Batch 256 at a benchmark shape: three whole images against the oracle, and, at any size,
-    the interior equals the +1-padded result while the border differs by an image-independent
+    """Batch 256 at a benchmark shape: every output against the oracle, and, at any size, the
+    interior equals the +1-padded result while the border differs by an image-independent
     amount."""
     L = wl.BIREAL18_BODY[0]
     N = wl.CFG5_BATCH
@@ -411,8 +407,7 @@ def test_bconv2d_zeropad_full_batch_layer(dabnn, oracle):
     wp = dabnn.pack_weights(gpu(wf))
     y0 = dabnn.bconv2d_zeropad(a, wp, L.Cin, L.stride, 1).cpu().numpy()
     y1 = dabnn.bconv2d(a, wp, L.Cin, L.stride, 1).cpu().numpy()
-    for n in (0, N // 2, N - 1):
-        assert np.array_equal(y0[n:n + 1], oracle.bconv2d_zeropad(x[n:n + 1], wf, L.stride, 1))
+    assert np.array_equal(y0, oracle.bconv2d_zeropad(x, wf, L.stride, 1))
     d = y1 - y0
     assert not d[:, 1:-1, 1:-1, :].any()
     assert np.array_equal(d, np.broadcast_to(d[:1], d.shape))
@@ -655,8 +650,8 @@ def test_cfg5_chain_small_batch(dabnn, oracle):
 
 @pytest.mark.parametrize("li", range(16))
 def test_cfg5_full_batch_layers(dabnn, oracle, li):
-    """Batch 256, the launch configuration the benchmark times.  Packed words are compared in
-    full; conv outputs on 200k sampled positions plus three whole images (first, middle, last)."""
+    """Batch 256, the launch configuration the benchmark times: every packed word and every
+    convolution output of all 256 images against the oracle."""
     L = wl.BIREAL18_BODY[li]
     N = wl.CFG5_BATCH
     print("cfg5 full", li, L, flush=True)
@@ -665,17 +660,11 @@ def test_cfg5_full_batch_layers(dabnn, oracle, li):
     a_gpu = dabnn.bitpack(gpu(x))
     assert np.array_equal(words(a_gpu), oracle.bitpack(x))
     y_gpu = dabnn.bconv2d(a_gpu, dabnn.pack_weights(gpu(wf)), L.Cin, L.stride, 1).cpu().numpy()
-    A, Wt = oracle.sign(x), oracle.sign(wf)
-    rng = np.random.default_rng(li)
-    S = 200_000
-    idx = np.stack([rng.integers(0, N, S), rng.integers(0, L.Ho, S), rng.integers(0, L.Wo, S),
-                    rng.integers(0, L.Cout, S)], axis=1).astype(np.int32)
-    want = oracle.bconv2d_at(A, Wt, idx, L.stride, 1)
-    assert np.array_equal(y_gpu[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]], want)
-    for n in (0, N // 2, N - 1):
-        assert np.array_equal(y_gpu[n:n + 1], oracle.bconv2d_signed(A[n:n + 1], Wt, L.stride, 1))
-    # properties that hold at any size: parity of K and the bound |y| <= K
-    assert np.all((y_gpu - L.K) % 2 == 0) and np.abs(y_gpu).max() <= L.K
+    want = oracle.bconv2d(x, wf, L.stride, 1)
+    assert y_gpu.shape == want.shape
+    if not np.array_equal(y_gpu, want):
+        bad = np.argwhere(y_gpu != want)
+        raise AssertionError(f"{len(bad)} of {want.size} outputs differ, first at {bad[0]}")
 
 
 # ------------------------------------------------------------------------ streams and HIP graphs
