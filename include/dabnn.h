@@ -76,15 +76,19 @@ typedef enum {
  * call or the next.
  */
 typedef enum {
-    DABNN_OPT_AREG_SLOTS = 0,      /* n > 0: split DABNN_ALGO_AREG work as if the device had n resident wavefronts */
-    DABNN_OPT_AREG_TAIL = 1,       /* uneven remainder of the split as small pieces: 1 never, 2 always */
-    DABNN_OPT_AREG_STORE = 2,      /* output store of DABNN_ALGO_AREG: 1 direct 16-byte stores, 16 or 32
-                                      channels transposed through LDS (ignored if Cout is no multiple) */
+    DABNN_OPT_AREG_SLOTS = 0,      /* n > 0: cut the work of a DABNN_ALGO_AREG launch into n ranges (wavefronts) */
+    DABNN_OPT_AREG_TAIL = 1,       /* uneven remainder of that split handed out as small pieces: 1 never, 2 always */
+    DABNN_OPT_AREG_STORE = 2,      /* output store of DABNN_ALGO_AREG: 1 direct 16-byte stores, 16 channels
+                                      transposed through LDS (ignored if Cout is no multiple of 16) */
     DABNN_OPT_RES_CHANNELS = 3,    /* 16: 16-channel groups in dabnn_bconv2d_bn_residual's fused kernel */
     DABNN_OPT_WREG_PIXELS = 4,     /* 7 or 8: output pixels per task of DABNN_ALGO_WREG */
     DABNN_OPT_BGEMM_COLUMNS = 5,   /* 16: 16-column groups in dabnn_bgemm's fast kernel */
     DABNN_OPT_BITPACK_ROWWISE = 6, /* 1: the row-wise kernel for channel counts that are no multiple of 64 */
-    DABNN_OPT_COUNT = 7
+    DABNN_OPT_AREG_SPLIT = 7,      /* DABNN_ALGO_AREG kernels in which the four wavefronts of a workgroup share a
+                                      channel group (always used above 8 words per pixel, by default at 8 when
+                                      Cout % 16 == 0): 1 not below 9 words, 4 also at 4 words */
+    DABNN_OPT_AREG_RANGES_PER_SIMD = 8, /* n > 0: cut the work of a DABNN_ALGO_AREG launch into n ranges per SIMD */
+    DABNN_OPT_COUNT = 9
 } dabnn_option;
 
 /* Sets option `option` (a dabnn_option) to `value` and returns DABNN_OK, or DABNN_ERR_UNSUPPORTED

@@ -69,7 +69,7 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_set_option", "dabnn_get_option"]
 
 (OPT_AREG_SLOTS, OPT_AREG_TAIL, OPT_AREG_STORE, OPT_RES_CHANNELS, OPT_WREG_PIXELS, OPT_BGEMM_COLUMNS,
- OPT_BITPACK_ROWWISE) = range(7)
+ OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD) = range(9)
 
 
 def set_option(option, value):

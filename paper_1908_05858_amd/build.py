@@ -6,7 +6,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libdabnn.so")
 SOURCES = (["dabnn_api.hip", "bitpack.hip", "bconv.hip", "bconv_areg.hip", "bconv_zeropad.hip", "bgemm.hip", "bconv_mfma.hip"] +
-           [f"bconv_areg_cw{cw}_s{st}.hip" for cw in (8, 4, 2, 1) for st in (1, 2)])
+           [f"bconv_areg_cw{cw}_s{st}.hip" for cw in (8, 7, 6, 5, 4, 3, 2, 1) for st in (1, 2)] +
+           [f"bconv_areg_split_cw{cw}.hip" for cw in (4, 3, 2, 1)])
+AREG_UNITS = [s for s in SOURCES if s.startswith("bconv_areg_") and "_cw" in s]
 # -packed-fp32-ops is switched off for every HIP translation unit of this project.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -16,7 +18,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "
 # whose operations must round separately: no contraction into fused multiply-adds in that file.
 EXTRA_FLAGS = {"bitpack.hip": ["-ffp-contract=off"]}
 # ... and so does the BN + shortcut epilogue of the activation-stationary convolution kernels.
-EXTRA_FLAGS.update({f"bconv_areg_cw{cw}_s{st}.hip": ["-ffp-contract=off"] for cw in (1, 2, 4, 8) for st in (1, 2)})
+EXTRA_FLAGS.update({src: ["-ffp-contract=off"] for src in AREG_UNITS})
 
 
 def build_library(verbose=False):

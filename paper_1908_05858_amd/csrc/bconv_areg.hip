@@ -1,5 +1,9 @@
-// Dispatch of the activation-stationary binary convolution family (kernels: bconv_areg_kernel.h,
-// instantiated per word count in bconv_areg_cw<Cw>.hip).
+// Dispatch of the activation-stationary binary convolution family.  Kernels with one wavefront
+// per channel group: bconv_areg_kernel.h, instantiated per word count and stride in
+// bconv_areg_cw<Cw>_s<stride>.hip (up to 8 words per pixel).  Kernels in which the four wavefronts
+// of a workgroup share a group: bconv_areg_split_kernel.h, instantiated in
+// bconv_areg_split_cw<n>.hip (more than 8 words per pixel, as a few launches that add up).
+#include "kernel_util.h"
 #include "launch.h"
 
 namespace dabnn {
@@ -14,25 +18,49 @@ namespace dabnn {
                                         hipStream_t stream, const float* scale,                   \
                                         const float* shift, const float* r, float* x_out,         \
                                         uint64_t* bits);
-DABNN_DECLARE(1, 1) DABNN_DECLARE(1, 2) DABNN_DECLARE(2, 1) DABNN_DECLARE(2, 2)
-DABNN_DECLARE(4, 1) DABNN_DECLARE(4, 2) DABNN_DECLARE(8, 1) DABNN_DECLARE(8, 2)
+#define DABNN_DECLARE_BOTH(CW) DABNN_DECLARE(CW, 1) DABNN_DECLARE(CW, 2)
+DABNN_DECLARE_BOTH(1) DABNN_DECLARE_BOTH(2) DABNN_DECLARE_BOTH(3) DABNN_DECLARE_BOTH(4)
+DABNN_DECLARE_BOTH(5) DABNN_DECLARE_BOTH(6) DABNN_DECLARE_BOTH(7) DABNN_DECLARE_BOTH(8)
+#undef DABNN_DECLARE_BOTH
 #undef DABNN_DECLARE
+#define DABNN_DECLARE_SPLIT(C)                                                                     \
+    hipError_t launch_split_cw##C(const uint32_t* a, const uint32_t* w, int32_t* y, int cw_total,  \
+                                  int word0, bool first, int active_waves, const ConvShape& s,    \
+                                  hipStream_t stream);
+DABNN_DECLARE_SPLIT(1) DABNN_DECLARE_SPLIT(2) DABNN_DECLARE_SPLIT(3) DABNN_DECLARE_SPLIT(4)
+#undef DABNN_DECLARE_SPLIT
 
 // The kernels address a window tap as the tensor base plus a 32-bit BYTE offset, and (on the
 // direct-store path) the output with 32-bit element offsets: the packed activation tensor must
-// stay below 4 GiB and the output below 2^31 elements.  Larger tensors run the other families,
-// which index with size_t.
+// stay below 4 GiB and the output below 2^31 elements.  The split kernels address the filters the
+// same way (below 4 GiB).  Larger tensors run the other families, which index with size_t.
 static bool areg_offsets_fit(const ConvShape& s)
 {
     const int64_t act_bytes = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 8;
     const int64_t out_elems = static_cast<int64_t>(s.N) * s.Ho * s.Wo * s.Cout;
-    return act_bytes < (int64_t{1} << 32) && out_elems < (int64_t{1} << 31);
+    const int64_t filter_bytes = static_cast<int64_t>(s.Cout) * 72 * s.Cw;
+    return act_bytes < (int64_t{1} << 32) && out_elems < (int64_t{1} << 31) &&
+           filter_bytes < (int64_t{1} << 32);
 }
+
+static bool areg_geometry(const ConvShape& s)
+{
+    return s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) && areg_offsets_fit(s);
+}
+
+// Calls F(CW, S) for the shape's word count (1..8) and stride.
+#define DABNN_SWITCH_CW_S(s, F)                                       \
+    switch ((s).Cw * 2 + ((s).stride == 2 ? 1 : 0)) {                 \
+        case 2: F(1, 1); case 3: F(1, 2); case 4: F(2, 1); case 5: F(2, 2);     \
+        case 6: F(3, 1); case 7: F(3, 2); case 8: F(4, 1); case 9: F(4, 2);     \
+        case 10: F(5, 1); case 11: F(5, 2); case 12: F(6, 1); case 13: F(6, 2); \
+        case 14: F(7, 1); case 15: F(7, 2); case 16: F(8, 1); case 17: F(8, 2); \
+        default: return hipErrorNotSupported;                         \
+    }
 
 bool bconv_bnsign_areg_supports(const ConvShape& s)
 {
-    return areg_offsets_fit(s) && s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) &&
-           (s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8) && s.Cout % 64 == 0;
+    return areg_geometry(s) && s.Cw <= 8 && s.Cout % 64 == 0;
 }
 
 hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const int32_t* thr,
@@ -44,20 +72,9 @@ hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const 
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
     const uint2* f2 = reinterpret_cast<const uint2*>(flip);
-    switch (s.Cw) {
-        case 1:
-            return s.stride == 1 ? launch_bits_cw1_s1(a32, w32, out, s, stream, thr, f2)
-                                 : launch_bits_cw1_s2(a32, w32, out, s, stream, thr, f2);
-        case 2:
-            return s.stride == 1 ? launch_bits_cw2_s1(a32, w32, out, s, stream, thr, f2)
-                                 : launch_bits_cw2_s2(a32, w32, out, s, stream, thr, f2);
-        case 4:
-            return s.stride == 1 ? launch_bits_cw4_s1(a32, w32, out, s, stream, thr, f2)
-                                 : launch_bits_cw4_s2(a32, w32, out, s, stream, thr, f2);
-        default:
-            return s.stride == 1 ? launch_bits_cw8_s1(a32, w32, out, s, stream, thr, f2)
-                                 : launch_bits_cw8_s2(a32, w32, out, s, stream, thr, f2);
-    }
+#define DABNN_CASE(CW, S) return launch_bits_cw##CW##_s##S(a32, w32, out, s, stream, thr, f2)
+    DABNN_SWITCH_CW_S(s, DABNN_CASE)
+#undef DABNN_CASE
 }
 
 bool bconv_bn_residual_areg_supports(const ConvShape& s, const void* scale, const void* shift,
@@ -77,26 +94,19 @@ hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, c
         return hipErrorNotSupported;
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
-#define DABNN_CASE(CW)                                                                             \
-    return s.stride == 1 ? launch_res_cw##CW##_s1(a32, w32, s, stream, scale, shift, r, x_out, bits) \
-                         : launch_res_cw##CW##_s2(a32, w32, s, stream, scale, shift, r, x_out, bits)
-    switch (s.Cw) {
-        case 1: DABNN_CASE(1);
-        case 2: DABNN_CASE(2);
-        case 4: DABNN_CASE(4);
-        default: DABNN_CASE(8);
-    }
+#define DABNN_CASE(CW, S) return launch_res_cw##CW##_s##S(a32, w32, s, stream, scale, shift, r, x_out, bits)
+    DABNN_SWITCH_CW_S(s, DABNN_CASE)
 #undef DABNN_CASE
 }
 
 bool bconv_areg_supports(const ConvShape& s, const void* y)
 {
-    if (!(s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2)))
+    if (!areg_geometry(s) || (reinterpret_cast<uintptr_t>(y) & 15) != 0)
         return false;
-    if (!(s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8))
-        return false;
-    const int cg = (s.Cw == 1) ? 8 : 4;
-    return areg_offsets_fit(s) && s.Cout % cg == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+    if (s.Cw > 8)
+        return s.Cout % 16 == 0;   // the split kernels: several launches that add up
+    // direct stores take 4 channels per group, 8 when the word count is odd
+    return s.Cout % ((s.Cw % 2) ? 8 : 4) == 0;
 }
 
 hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, const ConvShape& s,
@@ -106,20 +116,40 @@ hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, c
         return hipErrorNotSupported;
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
-    switch (s.Cw) {
-        case 1:
-            return s.stride == 1 ? launch_areg_cw1_s1(a32, w32, y, s, stream)
-                                 : launch_areg_cw1_s2(a32, w32, y, s, stream);
-        case 2:
-            return s.stride == 1 ? launch_areg_cw2_s1(a32, w32, y, s, stream)
-                                 : launch_areg_cw2_s2(a32, w32, y, s, stream);
-        case 4:
-            return s.stride == 1 ? launch_areg_cw4_s1(a32, w32, y, s, stream)
-                                 : launch_areg_cw4_s2(a32, w32, y, s, stream);
-        default:
-            return s.stride == 1 ? launch_areg_cw8_s1(a32, w32, y, s, stream)
-                                 : launch_areg_cw8_s2(a32, w32, y, s, stream);
+    // 8 words per pixel: both kernel kinds take the same time at batch 256 (62 us per 59 G-op
+    // layer); the four-wavefront kernel writes whole 64-byte runs where the one-wavefront kernel's
+    // direct stores cost 2.25 times the output bytes in HBM writes, so it is the default there.
+    // Option DABNN_OPT_AREG_SPLIT: 4 forces it for 4 words as well, 1 never uses it below 9 words.
+    const int split_option = option(DABNN_OPT_AREG_SPLIT);
+    const bool split_fits = s.Cw % 4 == 0 && s.Cout % 16 == 0 && option(DABNN_OPT_AREG_STORE) != 1;
+    const bool use_split = s.Cw > 8 || (split_fits && split_option != 1 && (s.Cw == 8 || split_option == 4));
+    if (!use_split) {
+#define DABNN_CASE(CW, S) return launch_areg_cw##CW##_s##S(a32, w32, y, s, stream)
+        DABNN_SWITCH_CW_S(s, DABNN_CASE)
+#undef DABNN_CASE
     }
+    // More than 8 words per pixel: the K dimension is covered by several four-wavefront launches
+    // in a row, the first writing y = K - 2*P1, the others adding -2*Pi: 16, 12, 8 or 4 words at
+    // a time, and a last one over the 1 to 3 words that remain, in which only that many
+    // wavefronts of a workgroup have words to read.
+    int word0 = 0;
+    while (word0 < s.Cw) {
+        const int left = s.Cw - word0;
+        const int per_wave = left >= 16 ? 4 : (left >= 4 ? left / 4 : 1);
+        const int active = left >= 4 ? 4 : left;
+        const bool first = word0 == 0;
+        hipError_t e;
+        switch (per_wave) {
+            case 1: e = launch_split_cw1(a32, w32, y, s.Cw, word0, first, active, s, stream); break;
+            case 2: e = launch_split_cw2(a32, w32, y, s.Cw, word0, first, active, s, stream); break;
+            case 3: e = launch_split_cw3(a32, w32, y, s.Cw, word0, first, active, s, stream); break;
+            default: e = launch_split_cw4(a32, w32, y, s.Cw, word0, first, active, s, stream); break;
+        }
+        if (e != hipSuccess)
+            return e;
+        word0 += left >= 4 ? 4 * per_wave : left;
+    }
+    return hipSuccess;
 }
 
 }  // namespace dabnn

@@ -1,0 +1,6 @@
+// Activation-stationary binary convolution kernels: 6 packed 64-bit words per pixel, stride 2.
+#include "bconv_areg_kernel.h"
+
+namespace dabnn {
+DABNN_DEFINE_AREG_ENTRY_POINTS(6, 2)
+}  // namespace dabnn

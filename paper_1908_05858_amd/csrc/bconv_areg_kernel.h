@@ -13,114 +13,25 @@
 // Stores: a lane holds consecutive channels of ONE pixel, so a direct store writes 16 bytes per
 // lane at a stride of Cout*4 bytes -- 64 partial cache lines per instruction, which saturates the
 // L2 write path long before HBM.  When Cout is a multiple of 16 the kernel therefore finishes 16
-// (or 32) channels, transposes the 64 x 16 tile through a wavefront-private slice of LDS and
-// stores it so that neighbouring lanes write the 64 (or 128) contiguous bytes of one pixel.
+// channels, transposes the 64 x 16 tile through a wavefront-private slice of LDS and stores it so
+// that four neighbouring lanes write the 64 contiguous bytes of one pixel.
 //
-// This family suits layers with few words per pixel (small windows, small filters that stay in
-// the scalar cache); the filter-stationary family in bconv.hip suits the opposite case.
+// One wavefront holds a pixel's whole window here, which fits the register file up to 8 words per
+// pixel (144 window registers).  bconv_areg_split_kernel.h spreads the words of a pixel over the
+// four wavefronts of a workgroup and covers any word count.
 #pragma once
-#include "kernel_util.h"
-#include "launch.h"
+#include "bconv_areg_common.h"
+
+#include <algorithm>
 
 namespace dabnn {
 namespace {
 
-// acc[q] += sum_{d<3} popcount(w[q][d] ^ a[d]) for four output channels q.  w sits in SGPRs
-// (written by scalar loads only: a VALU-written SGPR would need wait states the compiler cannot
-// see inside the assembly), a in VGPRs.  Four independent chains hide the VALU latency.
-template <bool FIRST>
-__device__ __forceinline__ void xor_popc_4x3(int* acc, const uint32_t* a, const uint32_t* w0,
-                                             const uint32_t* w1, const uint32_t* w2,
-                                             const uint32_t* w3)
-{
-    uint32_t t0, t1, t2, t3;
-#define DABNN_TAIL                                                                      \
-    "v_xor_b32 %4, %12, %9\n\t"                                                         \
-    "v_xor_b32 %5, %15, %9\n\t"                                                         \
-    "v_xor_b32 %6, %18, %9\n\t"                                                         \
-    "v_xor_b32 %7, %21, %9\n\t"                                                         \
-    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
-    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
-    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
-    "v_bcnt_u32_b32 %3, %7, %3\n\t"                                                     \
-    "v_xor_b32 %4, %13, %10\n\t"                                                        \
-    "v_xor_b32 %5, %16, %10\n\t"                                                        \
-    "v_xor_b32 %6, %19, %10\n\t"                                                        \
-    "v_xor_b32 %7, %22, %10\n\t"                                                        \
-    "v_bcnt_u32_b32 %0, %4, %0\n\t"                                                     \
-    "v_bcnt_u32_b32 %1, %5, %1\n\t"                                                     \
-    "v_bcnt_u32_b32 %2, %6, %2\n\t"                                                     \
-    "v_bcnt_u32_b32 %3, %7, %3"
-#define DABNN_INPUTS                                                                          \
-    "v"(a[0]), "v"(a[1]), "v"(a[2]), "s"(w0[0]), "s"(w0[1]), "s"(w0[2]), "s"(w1[0]), "s"(w1[1]), \
-        "s"(w1[2]), "s"(w2[0]), "s"(w2[1]), "s"(w2[2]), "s"(w3[0]), "s"(w3[1]), "s"(w3[2])
-    if constexpr (FIRST) {
-        // the accumulators start here: the first popcounts add to the constant 0
-        asm("v_xor_b32 %4, %11, %8\n\t"
-            "v_xor_b32 %5, %14, %8\n\t"
-            "v_xor_b32 %6, %17, %8\n\t"
-            "v_xor_b32 %7, %20, %8\n\t"
-            "v_bcnt_u32_b32 %0, %4, 0\n\t"
-            "v_bcnt_u32_b32 %1, %5, 0\n\t"
-            "v_bcnt_u32_b32 %2, %6, 0\n\t"
-            "v_bcnt_u32_b32 %3, %7, 0\n\t" DABNN_TAIL
-            : "=&v"(acc[0]), "=&v"(acc[1]), "=&v"(acc[2]), "=&v"(acc[3]), "=&v"(t0), "=&v"(t1),
-              "=&v"(t2), "=&v"(t3)
-            : DABNN_INPUTS);
-    } else {
-        asm("v_xor_b32 %4, %11, %8\n\t"
-            "v_xor_b32 %5, %14, %8\n\t"
-            "v_xor_b32 %6, %17, %8\n\t"
-            "v_xor_b32 %7, %20, %8\n\t"
-            "v_bcnt_u32_b32 %0, %4, %0\n\t"
-            "v_bcnt_u32_b32 %1, %5, %1\n\t"
-            "v_bcnt_u32_b32 %2, %6, %2\n\t"
-            "v_bcnt_u32_b32 %3, %7, %3\n\t" DABNN_TAIL
-            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
-              "=&v"(t2), "=&v"(t3)
-            : DABNN_INPUTS);
-    }
-#undef DABNN_TAIL
-#undef DABNN_INPUTS
-}
-
-// y = K - 2 * diff as one v_mad_i32_i24 (diff <= K < 2^23).  K is a kernel argument, so the SGPR
-// it sits in is written by a scalar load.
-__device__ __forceinline__ int finish_output(int diff, int K)
-{
-    int y;
-    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(y) : "v"(diff), "s"(K));
-    return y;
-}
-
-// Outputs are written once and never read by this kernel.  The transposed path stores whole
-// 64- or 128-byte runs, so it stores non-temporally (streaming through L2); the direct path
-// writes 16-byte pieces of a line at different times and leaves it to L2 to merge them.
-typedef int v4i __attribute__((ext_vector_type(4)));
-template <bool STREAM>
-__device__ __forceinline__ void store_out4(void* dst, const int4& o)
-{
-    v4i v = {o.x, o.y, o.z, o.w};
-    if constexpr (STREAM)
-        __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(dst));
-    else
-        *reinterpret_cast<v4i*>(dst) = v;
-}
-
-// Fused threshold: bits = (bits << 1) | (y < thr) for one output channel, with y = K - 2d (d the
-// popcount sum) and kt = K - thr:  y < thr  <=>  kt - 2d < 0.  Plain VALU arithmetic: the sign bit
-// of kt - 2d is shifted in with v_alignbit_b32, no lane mask ever goes through an SGPR pair.
-__device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
-{
-    const int t = kt - 2 * d;  // |kt|, 2d < 2^31: no overflow
-    bits = __builtin_amdgcn_alignbit(bits, static_cast<uint32_t>(t), 31);
-}
-
 // Geometry.  A group = CG output channels of one 64-pixel tile: the unit of work distribution
 // and of the output stores.  It is consumed as CG/4 quads of channels; a quad's K dimension
 // (18*Cw dwords) goes through the scalar-load software pipeline in units of 4 channels x 6 dwords.
-//   TR = 16 or 32 (transposed store through LDS): CG = TR.   TR = 0, direct 16-byte stores:
-//   CG = 8 (Cw = 1) or 4.   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
+//   TR = 16 (transposed store through LDS): CG = 16.   TR = 0, direct 16-byte stores:
+//   CG = 4, or 8 when Cw is odd (which keeps the unit count even).   TR = kBits: fused threshold + bit-pack output, CG = 16 (a quarter of
 //   an output word).
 constexpr int kBits = -1;
 constexpr int kRes = -3;    // fused BN + shortcut epilogue: float z and its packed sign bits
@@ -138,17 +49,6 @@ struct WindowArgs {
     uint32_t wo_mul, wo_shift;      // division constants of Wo
 };
 
-// floor(n / d) for any 32-bit n, with mul = floor(2^32 * (2^L - d) / d) + 1 and shift = L - 1,
-// L = ceil(log2 d) (d = 1: mul = 0 would need a 33-bit step, so the host passes shift = 32,
-// which selects the identity).
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t shift)
-{
-    if (shift == 32)
-        return n;
-    const uint32_t t = __umulhi(mul, n);
-    return (t + ((n - t) >> 1)) >> shift;
-}
-
 // Extra operands of the kRes mode.  It is the FIRST kernel parameter, so it sits at offset 0 of
 // the kernel-argument segment and the epilogue can fetch its fields from there with scalar loads
 // when it needs them, instead of holding ten more SGPRs through the main loop.
@@ -160,13 +60,12 @@ struct ResArgs {
     uint16_t* bits16;     // the packed output viewed as [N*Ho*Wo][Cout/16] half-words
 };
 constexpr int kTailTR = 16;  // the store mode whose uneven remainder is split into small pieces
-constexpr int kDC = 6;
 template <int CW, int TR>
 struct AregGeom {
     static constexpr int D = 2 * CW;
     static constexpr int KD = 18 * CW;
     static constexpr int CG =
-        TR > 0 ? TR : (TR == kRes32 ? 32 : ((TR == kBits || TR == kRes) ? 16 : (CW == 1 ? 8 : 4)));
+        TR > 0 ? TR : (TR == kRes32 ? 32 : ((TR == kBits || TR == kRes) ? 16 : (CW % 2 ? 8 : 4)));
     static constexpr int CHUNKS = KD / kDC;            // units per quad
     static constexpr int UNITS = (CG / 4) * CHUNKS;    // units per group (always even)
     static constexpr int SB = 4 * kDC;                 // SGPRs per unit buffer
@@ -258,10 +157,14 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
                 const uint32_t off =
                     v ? static_cast<uint32_t>(top_left + i * W + j) * ((2 * CW) * 4u) : 0u;
                 const char* src = base + off;
-                if constexpr ((2 * CW) == 2) {
-                    const uint2 u = *reinterpret_cast<const uint2*>(src);
-                    areg[(i * 3 + j) * 2 + 0] = u.x & keep;
-                    areg[(i * 3 + j) * 2 + 1] = u.y & keep;
+                if constexpr ((2 * CW) % 4 != 0) {
+                    // an odd number of words: pixels are 8-byte aligned only, 8-byte loads
+#pragma unroll
+                    for (int d = 0; d < (2 * CW); d += 2) {
+                        const uint2 u = *reinterpret_cast<const uint2*>(src + d * 4);
+                        areg[(i * 3 + j) * (2 * CW) + d + 0] = u.x & keep;
+                        areg[(i * 3 + j) * (2 * CW) + d + 1] = u.y & keep;
+                    }
                 } else {
 #pragma unroll
                     for (int d = 0; d < (2 * CW); d += 4) {
@@ -545,21 +448,6 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     }
 }
 
-// Constants of fast_div for the divisor d >= 1.
-inline void division_constants(uint32_t d, uint32_t& mul, uint32_t& shift)
-{
-    if (d == 1) {
-        mul = 0;
-        shift = 32;
-        return;
-    }
-    uint32_t L = 0;
-    while ((uint64_t{1} << L) < d)
-        ++L;  // L = ceil(log2 d) >= 1
-    mul = static_cast<uint32_t>(((uint64_t{1} << 32) * ((uint64_t{1} << L) - d)) / d + 1);
-    shift = L - 1;
-}
-
 template <int CW, int S, int TR>
 hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                             hipStream_t stream, const int32_t* thr = nullptr,
@@ -576,10 +464,23 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     if (n_groups64 > 0x3fffffff)
         return hipErrorNotSupported;
     const int n_groups = static_cast<int>(n_groups64);
-    // Exactly the resident wavefront slots; every wavefront gets the same number of groups
-    // (+-1), so the launch is one balanced round.
-    int64_t ranges = static_cast<int64_t>(blocks_per_cu) * device_cu_count() * 4;
-    const int forced_slots = option(DABNN_OPT_AREG_SLOTS);  // > 0: pretend a chip with that many slots
+    // The work is cut into contiguous ranges of groups, one per wavefront of the launch, every
+    // range the same length (+-1).  A SIMD serves its oldest wavefront first, so wavefronts with
+    // equal ranges do not end together: with exactly as many ranges as wavefronts fit the chip,
+    // a SIMD runs the second half of the launch with ever fewer wavefronts to pick from.  With
+    // more (shorter) ranges than resident wavefronts the hardware's dispatcher hands the rest out
+    // as slots free up, which keeps every SIMD full until shortly before the end.  Measured at
+    // batch 256 (ranges per SIMD: time): 1 word per pixel 7: 63 us, 10: 56 us; 4 words 4: 56 us,
+    // 7: 55 us; 8 words 2: 63 us, 7: 58 us, 12: 61 us.  A whole number of ranges per SIMD keeps
+    // the SIMDs' shares equal.
+    const int simds = device_cu_count() * 4;
+    int64_t per_simd = std::max(7, blocks_per_cu + 3);
+    if (option(DABNN_OPT_AREG_RANGES_PER_SIMD) > 0)
+        per_simd = option(DABNN_OPT_AREG_RANGES_PER_SIMD);
+    if (per_simd * simds > n_groups)
+        per_simd = std::max<int64_t>(n_groups / simds, 1);
+    int64_t ranges = per_simd * simds;
+    const int forced_slots = option(DABNN_OPT_AREG_SLOTS);  // > 0: that many ranges
     if (forced_slots > 0)
         ranges = forced_slots;
     if (ranges > n_groups)
@@ -618,17 +519,15 @@ template <int CW, int S>
 hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const ConvShape& s,
                          hipStream_t stream)
 {
-    // Transposing 32 channels writes whole 128-byte lines (HBM write traffic equals the
-    // algorithmic bytes) but costs registers and LDS; 16 channels (64-byte runs, 8-18 % extra
-    // write traffic) is the faster choice at the Bi-Real-18 shapes.  With 8 words per pixel
-    // (K = 4608) the output rate is so low that the direct store wins.
-    int tr = (CW <= 4 && s.Cout % 16 == 0) ? 16 : 0;
-    const int forced = option(DABNN_OPT_AREG_STORE);  // 0 as above, 1 direct, 16 / 32 transposed
+    // 16 channels transposed through LDS (64-byte runs) where Cout allows it.  With 8 words per
+    // pixel (K = 4608) the output rate is so low that the direct store, which needs no LDS and
+    // fewer registers, wins.
+    int tr = (CW != 8 && s.Cout % 16 == 0) ? 16 : 0;
+    const int forced = option(DABNN_OPT_AREG_STORE);  // 0 as above, 1 direct, 16 transposed
     if (forced == 1)
         tr = 0;
-    else if ((forced == 16 && s.Cout % 16 == 0) || (forced == 32 && s.Cout % 32 == 0))
-        tr = forced;
-    if (tr == 32) return launch_areg_inst<CW, S, 32>(a, w, y, s, stream);
+    else if (forced == 16 && s.Cout % 16 == 0)
+        tr = 16;
     if (tr == 16) return launch_areg_inst<CW, S, 16>(a, w, y, s, stream);
     return launch_areg_inst<CW, S, 0>(a, w, y, s, stream);
 }

@@ -47,14 +47,24 @@ inline int device_cu_count()
     return cus;
 }
 
-// Resident workgroups of 256 threads per CU for a kernel, queried once.
+// Resident workgroups of 256 threads per CU for a kernel (one wavefront per SIMD each), found
+// once.  The runtime's occupancy query is the upper bound; measured on MI355X, wavefronts of
+// launches sized by it alone start late when it answers 8, or 7 for a kernel with 65 to 72 vector
+// registers: what is resident at once is at most 7 wavefronts per SIMD, with registers counted in
+// blocks of 16.  A launch of exactly the resident size is what the balanced work splits assume.
 template <class Kernel>
 inline int resident_blocks_per_cu(Kernel kernel)
 {
     int nb = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb <= 0)
         nb = 2;
-    return nb;
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) == hipSuccess && attr.numRegs > 0) {
+        const int by_registers = 512 / ((attr.numRegs + 15) / 16 * 16);
+        if (by_registers >= 1 && by_registers < nb)
+            nb = by_registers;
+    }
+    return nb > 7 ? 7 : nb;
 }
 
 }  // namespace dabnn

@@ -98,17 +98,35 @@ def test_tensors_past_the_32bit_byte_offsets_leave_the_activation_stationary_fam
     assert lib.dabnn_bconv2d_pick_algo(1, 8192, 8192, 512, 16, 3, 3, 1, 1) != AREG
 
 
+def test_every_word_count_has_a_tuned_kernel(lib):
+    """3x3 convolutions of any channel count resolve to the activation-stationary family: one
+    launch up to 8 words per pixel, several that add up above."""
+    AREG = 3
+    for Cin in (1, 64, 100, 160, 192, 320, 384, 448, 512, 576, 704, 768, 1024, 1088, 2048, 4100):
+        for Cout, stride in ((64, 1), (16, 2), (48, 1)):
+            assert lib.dabnn_bconv2d_pick_algo(4, 14, 14, Cin, Cout, 3, 3, stride, 1) == AREG, (Cin, Cout)
+    # direct stores (Cout % 16 != 0) exist for up to 8 words per pixel: 4-channel groups, 8 where
+    # the word count is odd; everything else is left to the other families
+    assert lib.dabnn_bconv2d_pick_algo(4, 14, 14, 64, 12, 3, 3, 1, 1) != AREG
+    assert lib.dabnn_bconv2d_pick_algo(4, 14, 14, 128, 12, 3, 3, 1, 1) == AREG
+    assert lib.dabnn_bconv2d_pick_algo(4, 14, 14, 320, 24, 3, 3, 1, 1) == AREG
+    assert lib.dabnn_bconv2d_pick_algo(4, 14, 14, 576, 24, 3, 3, 1, 1) != AREG
+
+
 def test_options(lib):
     """Options default to 0, are set and read back through the C ABI, and unknown ones are refused;
     the library ignores the environment."""
     import os
-    for opt in range(7):
+    n_options = 9
+    text = open(os.path.join(ROOT, "include", "dabnn.h")).read()
+    assert f"DABNN_OPT_COUNT = {n_options}" in text
+    for opt in range(n_options):
         assert lib.dabnn_get_option(opt) == 0
     assert lib.dabnn_set_option(2, 16) == 0 and lib.dabnn_get_option(2) == 16
     assert lib.dabnn_set_option(2, 0) == 0 and lib.dabnn_get_option(2) == 0
-    assert lib.dabnn_set_option(7, 1) == 4 and lib.dabnn_set_option(-1, 1) == 4
+    assert lib.dabnn_set_option(n_options, 1) == 4 and lib.dabnn_set_option(-1, 1) == 4
     assert lib.dabnn_set_option(0, -5) == 4
-    assert lib.dabnn_get_option(7) == -1
+    assert lib.dabnn_get_option(n_options) == -1
     src = os.path.join(ROOT, "paper_1908_05858_amd", "csrc")
     for name in os.listdir(src):
         assert "getenv" not in open(os.path.join(src, name)).read(), name

@@ -333,12 +333,13 @@ def test_odd_shapes_tuned(dabnn, oracle, shape, algo):
     run_conv(dabnn, oracle, *shape, seed=999 + sum(shape), algo=algo)
 
 
-@pytest.mark.parametrize("env", [("OPT_AREG_STORE", 1, 3), ("OPT_AREG_STORE", 16, 3), ("OPT_AREG_STORE", 32, 3),
+@pytest.mark.parametrize("env", [("OPT_AREG_STORE", 1, 3), ("OPT_AREG_STORE", 16, 3), ("OPT_AREG_SPLIT", 4, 3),
                                  ("OPT_WREG_PIXELS", 7, 2), ("OPT_WREG_PIXELS", 8, 2)],
                          ids=lambda e: f"{e[0]}={e[1]}")
 def test_kernel_variants(dabnn, oracle, env, option):
-    """Every store variant of the activation-stationary family and both chunk widths of the
-    filter-stationary family, forced through the library's options."""
+    """Both store variants of the activation-stationary family, its four-wavefront kernels at 4
+    and 8 words per pixel, and both chunk widths of the filter-stationary family, forced through
+    the library's options."""
     name, value, algo = env
     option(getattr(dabnn, name), value)
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
@@ -352,11 +353,12 @@ def test_kernel_variants(dabnn, oracle, env, option):
 def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, option):
     """The split of (tile, channel group) pairs over wavefronts, with the wavefront count forced
     small so that ranges span several tiles, and the uneven remainder handed out either as whole
-    groups or as direct-store pieces."""
+    groups or as direct-store pieces; the four-wavefront kernels split over workgroups alike."""
     option(dabnn.OPT_AREG_SLOTS, slots)
     option(dabnn.OPT_AREG_TAIL, tail)
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
-                  (1, 23, 17, 64, 48, 3, 1, 1), (2, 7, 7, 512, 64, 3, 1, 1)]:
+                  (1, 23, 17, 64, 48, 3, 1, 1), (2, 7, 7, 512, 64, 3, 1, 1), (2, 9, 7, 320, 48, 3, 1, 1),
+                  (2, 6, 5, 1024, 32, 3, 1, 1), (1, 9, 9, 704, 32, 3, 2, 1)]:
         print("split", slots, tail, shape, flush=True)
         run_conv(dabnn, oracle, *shape, seed=1717 + slots + sum(shape), algo=3)
     shape = (2, 14, 14, 128, 128, 3, 1, 1)
@@ -366,6 +368,43 @@ def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, option):
     thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * 128)
     got = dabnn.bconv2d_bnsign(dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf)), thr, flip, 128, 1, 1)
     assert np.array_equal(words(got), oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, 1, 1))
+
+
+WORD_COUNT_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad: every kernel of the family and every split of K
+    (3, 14, 14, 160, 64, 3, 1, 1), (2, 9, 11, 192, 48, 3, 2, 1), (2, 14, 14, 320, 64, 3, 1, 1),
+    (3, 7, 9, 384, 32, 3, 1, 1), (2, 8, 8, 448, 64, 3, 2, 1), (2, 7, 7, 576, 64, 3, 1, 1),
+    (2, 6, 7, 640, 16, 3, 1, 1), (1, 9, 9, 704, 32, 3, 2, 1), (2, 7, 7, 768, 64, 3, 1, 1),
+    (2, 5, 6, 832, 32, 3, 1, 1), (2, 7, 7, 1024, 128, 3, 1, 1), (1, 6, 6, 1088, 32, 3, 1, 1),
+    (1, 5, 5, 2048, 32, 3, 1, 1), (1, 4, 6, 2240, 16, 3, 2, 1),
+    # Cout % 16 != 0: direct stores, up to 8 words per pixel
+    (2, 9, 9, 192, 24, 3, 1, 1), (2, 7, 7, 320, 40, 3, 1, 1), (2, 6, 6, 448, 8, 3, 2, 1),
+    (2, 7, 7, 500, 8, 3, 1, 1), (2, 6, 6, 384, 20, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", WORD_COUNT_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_every_word_count(dabnn, oracle, shape):
+    """Channel counts from 3 to 35 words per pixel run in the activation-stationary family: as one
+    launch, or as several launches over parts of the channels that add into y."""
+    print("words", shape, flush=True)
+    assert dabnn.pick_algo(*shape[:5], 3, 3, shape[6], shape[7]) == dabnn.ALGO_AREG
+    run_conv(dabnn, oracle, *shape, seed=6100 + sum(shape), algo=3)
+    run_conv(dabnn, oracle, *shape, seed=6200 + sum(shape), algo=0)
+
+
+def test_launches_that_add_into_y_follow_one_another(dabnn, oracle):
+    """Word counts above 8 run as launches that add into y: repeated calls into the same output
+    buffer (which then holds an old result, not zeros) must give the same values every time."""
+    shape = (3, 9, 9, 1216, 64, 3, 1, 1)          # 19 words: 16 + 3
+    N, H, W, Cin, Cout = shape[:5]
+    x = wl.activations((N, H, W, Cin), 8400)
+    wf = wl.weights((Cout, 3, 3, Cin), 8401)
+    a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+    want = oracle.bconv2d(x, wf, 1, 1)
+    out = torch.full(want.shape, 12345, dtype=torch.int32, device="cuda")
+    for rep in range(3):
+        dabnn.bconv2d(a, wp, Cin, 1, 1, out=out)
+        assert np.array_equal(out.cpu().numpy(), want), rep
 
 
 # ------------------------------------------------------------------- zero padding (ONNX Convolution)
