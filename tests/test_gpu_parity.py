@@ -392,6 +392,16 @@ def test_every_word_count(dabnn, oracle, shape):
     run_conv(dabnn, oracle, *shape, seed=6200 + sum(shape), algo=0)
 
 
+@pytest.mark.parametrize("Cin", [160, 320, 384, 448, 1024])
+def test_word_counts_at_batch_64(dabnn, oracle, Cin):
+    """3, 5, 6, 7 and 16 words per pixel at batch 64 (several ranges per SIMD, many tiles), every
+    output compared; the automatic choice must be the activation-stationary family."""
+    shape = (64, 14, 14, Cin, 256, 3, 1, 1)
+    print("words at batch 64", shape, flush=True)
+    assert dabnn.pick_algo(*shape[:5], 3, 3, 1, 1) == dabnn.ALGO_AREG
+    run_conv(dabnn, oracle, *shape, seed=6300 + Cin, algo=0)
+
+
 def test_launches_that_add_into_y_follow_one_another(dabnn, oracle):
     """Word counts above 8 run as launches that add into y: repeated calls into the same output
     buffer (which then holds an old result, not zeros) must give the same values every time."""
