@@ -16,7 +16,8 @@ Prints ONE JSON line.
                    stride-1 sweep at batch 1 and 64, the bit-pack shapes incl. C = 80 / 200, the
                    stride-2 layers at batch 128): microseconds, GOPS or GB/s, roofline fraction
                    and the oracle's time on the same tensors.  Never part of `value`.
-  fused_bnsign, bireal_block_chain, batch1_chain_latency, int8_mfma_comparison
+  fused_bnsign, bireal_block_chain, batch1_chain_latency, int8_mfma_comparison,
+  mfma_from_packed_bits_comparison
                    widened entry points on the same layers, timed after everything above.
   cpu_baseline     the CPU oracle on the same 16 layers, all host threads.
 """
@@ -271,7 +272,7 @@ def main():
 
     if not args.headline_only:
         result["configs"] = other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle)
-        widened_rows(result, args, binding, wl, np, torch, layers, N, acts, wps, ys, total_ops, wall_ms)
+        widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps, ys, total_ops, wall_ms, launch_us)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     if want_oracle:
@@ -402,7 +403,7 @@ def other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle):
     return out
 
 
-def widened_rows(result, args, binding, wl, np, torch, layers, N, acts, wps, ys, total_ops, wall_ms):
+def widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps, ys, total_ops, wall_ms, launch_us):
     """Widened entry points on the same 16 layers; reported beside the headline, never in it."""
     reps = max(4, args.steps // 4)
     # conv + BN threshold + bit-pack of the result in one kernel: packed words in, packed words out
@@ -517,6 +518,46 @@ def widened_rows(result, args, binding, wl, np, torch, layers, N, acts, wps, ys,
             "conv_only_frac_of_int8_mfma_peak": round(total_ops / (mfma_conv_ms * 1e-3) / 5.0e15, 4),
         }
         del w8s, a8s
+
+    # Second comparison row: the int8 matrix cores fed from the PACKED activations
+    # (dabnn_bconv2d_mfma; only the filters are expanded, ahead of time like they are packed ahead
+    # of time).  The step is the headline step with dabnn_bconv2d replaced by it; per layer, HIP
+    # event intervals of the same launches beside those of the XOR/popcount kernel.
+    if all(binding.mfma_weights_bytes(L.Cin, L.Cout) > 0 for L in layers):
+        wqs = [binding.prepare_weights_mfma(wps[li], L.Cin) for li, L in enumerate(layers)]
+
+        def bits_step(conv_only=False):
+            for li, L in enumerate(layers):
+                if not conv_only:
+                    binding.bitpack(xs[li], out=acts[li])
+                binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1, out=ys[li])
+        bits_ms = wall_ms(bits_step, reps)
+        bits_conv_ms = wall_ms(lambda: bits_step(conv_only=True), reps)
+        rows, seen = [], set()
+        for li, L in enumerate(layers):
+            key = (L.H, L.Cin, L.Cout, L.stride)
+            if key in seen:
+                continue
+            seen.add(key)
+            t_mfma, _ = launch_us(lambda: binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1, out=ys[li]))
+            t_valu, _ = launch_us(lambda: binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li]))
+            rows.append({"layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}", "mfma_us": round(t_mfma, 2),
+                         "mfma_frac_of_int8_peak": round(L.ops(N) / t_mfma / 1e6 / 5000.0, 4),
+                         "xor_popcount_us": round(t_valu, 2)})
+        result["mfma_from_packed_bits_comparison"] = {
+            "what": "the headline step with dabnn_bconv2d replaced by dabnn_bconv2d_mfma: int8 "
+                    "v_mfma_i32_32x32x32_i8 whose activation operand is expanded from the packed "
+                    "words inside the kernel (one AND per operand register) and whose filters are "
+                    "prepared once per model; same int32 outputs.  A comparison, not the method's "
+                    "path: the headline stays XOR + popcount",
+            "ms_per_step": round(bits_ms, 4),
+            "GOPS": round(total_ops / (bits_ms * 1e-3) / 1e9, 1),
+            "conv_only_ms_per_step": round(bits_conv_ms, 4),
+            "conv_only_GOPS": round(total_ops / (bits_conv_ms * 1e-3) / 1e9, 1),
+            "conv_only_frac_of_int8_mfma_peak": round(total_ops / (bits_conv_ms * 1e-3) / 5.0e15, 4),
+            "per_layer": rows,
+        }
+        del wqs
 
 
 if __name__ == "__main__":

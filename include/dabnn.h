@@ -88,7 +88,8 @@ typedef enum {
                                       channel group (always used above 8 words per pixel, by default at 8 when
                                       Cout % 16 == 0): 1 not below 9 words, 4 also at 4 words */
     DABNN_OPT_AREG_RANGES_PER_SIMD = 8, /* n > 0: cut the work of a DABNN_ALGO_AREG launch into n ranges per SIMD */
-    DABNN_OPT_COUNT = 9
+    DABNN_OPT_MFMA_PIXEL_BLOCKS = 9, /* dabnn_bconv2d_mfma: 2 or 4 blocks of 32 pixels per wavefront */
+    DABNN_OPT_COUNT = 10
 } dabnn_option;
 
 /* Sets option `option` (a dabnn_option) to `value` and returns DABNN_OK, or DABNN_ERR_UNSUPPORTED
@@ -247,6 +248,33 @@ int dabnn_im2col(const uint64_t *a, uint64_t *cols, int N, int H, int W, int Cin
  */
 int dabnn_expand_int8(const uint64_t *bits, int8_t *out, int64_t rows, int C, void *stream);
 int dabnn_bconv2d_int8(const int8_t *a8, const int8_t *w8, int32_t *y, int N, int H, int W, int Cin,
+                       int Cout, int kh, int kw, int stride, int pad, void *stream);
+
+/*
+ * Matrix-core route fed from the packed bits.  The same integers as dabnn_bconv2d (Sec. 2.1.2,
+ * Eq. 6-7), computed as an int8 matrix product: with a = 1 for an activation of -1 (else 0) and
+ * s = +-1 for the weights, y = sum_k (1 - 2 a_k) s_k = S - 2 * sum_k a_k s_k, S = sum_k s_k.  The
+ * activation operand is expanded from the packed words inside the kernel (one AND per operand
+ * register), so the activations stay packed in memory; only the filters are expanded, once per
+ * model, into the order in which the kernel consumes them.
+ *
+ * dabnn_mfma_weights_bytes: size in bytes of the prepared filter buffer for a layer, 0 if the
+ *   shape is outside what this route supports.
+ * dabnn_prepare_weights_mfma:
+ *   w  : u64 [Cout][3][3][Cin/64]  device, as written by dabnn_pack_weights
+ *   wq : dabnn_mfma_weights_bytes(...) bytes, device, 16-byte aligned, written completely
+ *        (int8 operands in kernel order, then S[Cout] as int32); owned by the caller.
+ * dabnn_bconv2d_mfma:
+ *   a  : u64 [N][H][W][Cin/64]     device, as written by dabnn_bitpack
+ *   wq : the prepared filters of the same layer shape
+ *   y  : i32 [N][Ho][Wo][Cout]     device, written completely.  Out-of-image taps count as +1.
+ * Supported: 3x3 kernels, stride 1 or 2, Cin in {64, 128, 256, 512}, Cout % 64 == 0 and at most
+ * 8192, packed activations below 2^31 dwords; DABNN_ERR_UNSUPPORTED otherwise (nothing launched).
+ */
+size_t dabnn_mfma_weights_bytes(int Cin, int Cout, int kh, int kw);
+int dabnn_prepare_weights_mfma(const uint64_t *w, void *wq, int Cin, int Cout, int kh, int kw,
+                               void *stream);
+int dabnn_bconv2d_mfma(const uint64_t *a, const void *wq, int32_t *y, int N, int H, int W, int Cin,
                        int Cout, int kh, int kw, int stride, int pad, void *stream);
 
 /*

@@ -49,6 +49,9 @@ def load():
     lib.dabnn_bconv2d_bn_residual.restype = i32
     lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
     lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
+    lib.dabnn_mfma_weights_bytes.argtypes, lib.dabnn_mfma_weights_bytes.restype = [i32] * 4, ctypes.c_size_t
+    lib.dabnn_prepare_weights_mfma.argtypes, lib.dabnn_prepare_weights_mfma.restype = [vp, vp] + [i32] * 4 + [vp], i32
+    lib.dabnn_bconv2d_mfma.argtypes, lib.dabnn_bconv2d_mfma.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
@@ -66,10 +69,11 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_bconv2d_bnsign", "dabnn_bn_thresholds", "dabnn_bconv2d_zeropad", "dabnn_bgemm", "dabnn_im2col",
            "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
            "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack", "dabnn_bconv2d_bn_residual",
-           "dabnn_set_option", "dabnn_get_option"]
+           "dabnn_set_option", "dabnn_get_option", "dabnn_mfma_weights_bytes",
+           "dabnn_prepare_weights_mfma", "dabnn_bconv2d_mfma"]
 
 (OPT_AREG_SLOTS, OPT_AREG_TAIL, OPT_AREG_STORE, OPT_RES_CHANNELS, OPT_WREG_PIXELS, OPT_BGEMM_COLUMNS,
- OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD) = range(9)
+ OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD, OPT_MFMA_PIXEL_BLOCKS) = range(10)
 
 
 def set_option(option, value):
@@ -301,6 +305,40 @@ def bconv2d_int8(a8, w8, stride=1, pad=0, out=None):
     _check(load().dabnn_bconv2d_int8(_dev(a8, torch.int8, "a8"), _dev(w8, torch.int8, "w8"),
                                      _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, kh, kw, stride,
                                      pad, _stream()), "dabnn_bconv2d_int8")
+    return out
+
+
+def mfma_weights_bytes(Cin, Cout, kh=3, kw=3):
+    """Bytes of the prepared filter buffer of dabnn_bconv2d_mfma; 0 for an unsupported layer."""
+    return load().dabnn_mfma_weights_bytes(Cin, Cout, kh, kw)
+
+
+def prepare_weights_mfma(w, Cin, out=None):
+    """Packed filters int64 [Cout, 3, 3, Cin/64] -> the uint8 buffer dabnn_bconv2d_mfma consumes
+    (int8 operands in kernel order followed by one int32 constant per output channel)."""
+    Cout, kh, kw, _ = w.shape
+    n = mfma_weights_bytes(Cin, Cout, kh, kw)
+    if n == 0:
+        raise DabnnError(4, "dabnn_mfma_weights_bytes")
+    if out is None:
+        out = torch.empty((n,), dtype=torch.uint8, device=w.device)
+    _check(load().dabnn_prepare_weights_mfma(_dev(w, torch.int64, "w"), _dev(out, torch.uint8, "out"),
+                                             Cin, Cout, kh, kw, _stream()), "dabnn_prepare_weights_mfma")
+    return out
+
+
+def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None):
+    """a: packed int64 [N,H,W,Cin/64]; wq: prepare_weights_mfma of the layer's 3x3 filters ->
+    int32 [N,Ho,Wo,Cout], the values of bconv2d, computed on the int8 matrix cores."""
+    N, H, W, _ = a.shape
+    Ho, Wo = conv_out_dim(H, 3, stride, pad), conv_out_dim(W, 3, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_mfma")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, Cout), dtype=torch.int32, device=a.device)
+    _check(load().dabnn_bconv2d_mfma(_dev(a, torch.int64, "a"), _dev(wq, torch.uint8, "wq"),
+                                     _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, 3, 3, stride, pad,
+                                     _stream()), "dabnn_bconv2d_mfma")
     return out
 
 

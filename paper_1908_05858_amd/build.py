@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libdabnn.so")
-SOURCES = (["dabnn_api.hip", "bitpack.hip", "bconv.hip", "bconv_areg.hip", "bconv_zeropad.hip", "bgemm.hip", "bconv_mfma.hip"] +
+SOURCES = (["dabnn_api.hip", "bitpack.hip", "bconv.hip", "bconv_areg.hip", "bconv_zeropad.hip", "bgemm.hip", "bconv_mfma.hip", "bconv_mfma_bits.hip"] +
            [f"bconv_areg_cw{cw}_s{st}.hip" for cw in (8, 7, 6, 5, 4, 3, 2, 1) for st in (1, 2)] +
            [f"bconv_areg_split_cw{cw}.hip" for cw in (4, 3, 2, 1)])
 AREG_UNITS = [s for s in SOURCES if s.startswith("bconv_areg_") and "_cw" in s]
@@ -21,8 +21,13 @@ EXTRA_FLAGS = {"bitpack.hip": ["-ffp-contract=off"]}
 EXTRA_FLAGS.update({src: ["-ffp-contract=off"] for src in AREG_UNITS})
 
 
-def build_library(verbose=False):
+def build_library(verbose=False, incremental=False):
+    """Compiles every translation unit and links the library.  `incremental` (a development
+    convenience) skips units whose object file is newer than the unit and every header."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    headers.append(os.path.join(os.path.dirname(HERE), "include", "dabnn.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
     objs = []
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
@@ -30,6 +35,9 @@ def build_library(verbose=False):
     for src in SOURCES:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
         objs.append(obj)
+        if incremental and os.path.exists(obj) and \
+                os.path.getmtime(obj) > max(newest_header, os.path.getmtime(os.path.join(CSRC, src))):
+            continue
         cmd = [hipcc] + HIPCC_FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

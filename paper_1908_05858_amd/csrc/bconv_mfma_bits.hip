@@ -1,0 +1,372 @@
+// Binary 3x3 convolution on the int8 matrix cores, fed from the PACKED bits (Sec. 2.1.2, Eq. 6-7
+// give the result; this file computes the same integers as a matrix product).
+//
+// With a = 1 for an activation of -1 (0 for +1) and s = +1 / -1 for a weight of +1 / -1,
+//     y = sum_k (1 - 2 a_k) s_k = S - 2 * sum_k a_k s_k,      S = sum_k s_k = K - 2 popcount(w),
+// so the convolution is one int8 product of 0/1 activations with +-1 weights plus a constant per
+// output channel; an out-of-image tap is a = 0 (+1), which is the all-zero word the packed tensor
+// already stands for.  The matrix instruction contracts 32 products whose order is free as long
+// as both operands agree on it, which makes the expansion of the activation bits cheap:
+//   lane (pixel m, half h) of a wavefront holds one 32-bit word x of the pixel's window;
+//   step j in {0, 1} of that word uses xs = x >> 4j, and operand register v in 0..3 is
+//   xs & (0x01010101 << v): byte b holds bit 4j + v + 8b of x, as the value 2^v.
+// One AND per operand register.  The weights are prepared once per model in exactly that order
+// (dabnn_prepare_weights_mfma): byte (h, v, b) of a step is s * 2^(3 - v), so every product is
+// +-8 a and the accumulator holds 8 * sum a s; y = S - acc / 4.
+//
+//   mfma_prepare_weights_kernel : packed filters -> [Cout/32][steps][64 lanes][16 B] int8, S[Cout]
+//   bconv_mfma_bits_kernel      : a wavefront owns 32*MB pixels x 32*NB channels (MB x NB
+//       v_mfma_i32_32x32x32_i8 accumulators); the four wavefronts of a workgroup own different
+//       pixels and the same channels, and share the weight operands through LDS (double-buffered
+//       stages of CH steps, one barrier per stage); the activation words come straight from the
+//       packed tensor (a few KB per tile, cache-resident) one stage ahead.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <type_traits>
+
+#include "kernel_util.h"
+#include "launch.h"
+
+namespace dabnn {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Order of the K dimension, shared by the two kernels.  A pixel's tap holds 2*CW dwords.  They are
+// consumed in R rounds of 2*W dwords; in a round the lanes of half h take dwords 2W*r + W*h + q,
+// q < W, and every dword feeds two steps (j = 0, 1).  Step index t = ((tap*R + r)*W + q)*2 + j.
+__host__ __device__ constexpr int mfma_w(int cw) { return cw < 4 ? cw : 4; }
+
+// One thread per (output channel, step, half, register): 4 bytes out.
+__global__ __launch_bounds__(256) void mfma_prepare_weights_kernel(
+    const uint32_t* __restrict__ wp, int8_t* __restrict__ wq, int32_t* __restrict__ sw, int Cout,
+    int Cw, int steps)
+{
+    const int W = mfma_w(Cw), R = Cw / W, D = 2 * Cw;
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t total = static_cast<int64_t>(Cout) * steps * 8;
+    if (idx < total) {
+        const int v = static_cast<int>(idx & 3);
+        const int h = static_cast<int>((idx >> 2) & 1);
+        const int64_t ct = idx >> 3;
+        const int t = static_cast<int>(ct % steps);
+        const int n = static_cast<int>(ct / steps);
+        const int j = t & 1;
+        const int u = t >> 1;  // (tap*R + r)*W + q
+        const int q = u % W;
+        const int r = (u / W) % R;
+        const int tap = u / (W * R);
+        const uint32_t x = wp[(static_cast<int64_t>(n) * 9 + tap) * D + 2 * W * r + W * h + q];
+        uint32_t out = 0;
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t bit = (x >> (4 * j + v + 8 * b)) & 1u;
+            const int val = (bit ? -1 : 1) * (8 >> v);
+            out |= (static_cast<uint32_t>(val) & 0xffu) << (8 * b);
+        }
+        // [n/32][t][lane = 32h + n%32][16 bytes = 4 registers]
+        const int64_t o = ((static_cast<int64_t>(n >> 5) * steps + t) * 64 + 32 * h + (n & 31)) * 16 + 4 * v;
+        *reinterpret_cast<uint32_t*>(wq + o) = out;
+    }
+    // S[n] = K - 2 * popcount of the filter's words (Cin % 64 == 0: no padding bits)
+    if (idx < Cout) {
+        const int n = static_cast<int>(idx);
+        int pop = 0;
+        for (int d = 0; d < 9 * D; ++d)
+            pop += __popc(wp[static_cast<int64_t>(n) * 9 * D + d]);
+        sw[n] = 9 * 64 * Cw - 2 * pop;
+    }
+}
+
+struct MfmaArgs {
+    int H, W, Ho, Wo, pad, Cout, total_pix;
+};
+
+template <int CW, int S, int MB, int NB>
+struct MfmaGeom {
+    static constexpr int W = mfma_w(CW);
+    static constexpr int R = CW / W;
+    static constexpr int D = 2 * CW;
+    static constexpr int STEPS = 18 * CW;
+    // steps per LDS stage: three taps (a window row) at one word per pixel, otherwise one round
+    static constexpr int CH = CW == 1 ? 6 : 2 * W;
+    static constexpr int STAGES = STEPS / CH;
+    static constexpr int UPS = CH / 2;                 // dwords a lane consumes per stage
+    static constexpr int STAGE_BYTES = CH * NB * 1024;
+    static constexpr int UNITS = STAGE_BYTES / 16 / 256;  // 16-byte copies per thread and stage
+    static_assert(STEPS % CH == 0 && STAGE_BYTES % (16 * 256) == 0, "stage geometry");
+};
+
+// MASKED = false: the tensor has at least 32*MB pixels, and a wavefront whose tile would reach
+// past the end computes the LAST 32*MB pixels instead (some of them a second time, with the same
+// results), so that no load or store needs a bounds check.  MASKED = true: fewer pixels than one
+// tile; rows past the end repeat the last pixel and are not stored.
+template <int CW, int S, int MB, int NB, bool MASKED>
+__global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __restrict__ a,
+                                                              const int8_t* __restrict__ wq,
+                                                              const int32_t* __restrict__ sw,
+                                                              int32_t* __restrict__ y,
+                                                              const MfmaArgs p)
+{
+    using G = MfmaGeom<CW, S, MB, NB>;
+    __shared__ __attribute__((aligned(16))) int8_t lds_b[2][G::STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    int pix0 = (blockIdx.x * 4 + wave) * (32 * MB);   // first pixel of this wavefront
+    if (!MASKED)
+        pix0 = min(pix0, p.total_pix - 32 * MB);
+    const int nblk0 = blockIdx.y * NB;                       // first 32-channel block
+
+    // Per pixel block: dword offset of the window's top-left tap (may lie outside the tensor; used
+    // only for taps inside the image) and one validity bit per tap.
+    int a_base[MB];
+    uint32_t a_valid[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int pc = min(pix0 + 32 * i + m, p.total_pix - 1);  // rows past the end repeat
+        const int n = pc / (p.Ho * p.Wo);
+        const int rem = pc - n * (p.Ho * p.Wo);
+        const int ho = rem / p.Wo;
+        const int hi0 = ho * S - p.pad;
+        const int wi0 = (rem - ho * p.Wo) * S - p.pad;
+        a_base[i] = ((n * p.H + hi0) * p.W + wi0) * G::D + G::W * h;
+        uint32_t mask = 0;
+#pragma unroll
+        for (int ti = 0; ti < 3; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < 3; ++tj)
+                if (static_cast<unsigned>(hi0 + ti) < static_cast<unsigned>(p.H) &&
+                    static_cast<unsigned>(wi0 + tj) < static_cast<unsigned>(p.W))
+                    mask |= 1u << (ti * 3 + tj);
+        a_valid[i] = mask;
+    }
+
+    // The activation dwords of stage st for this lane: raw[i][k], k < UPS.  A tap outside the image
+    // reads offset 0 and is cleared: both through an all-ones / all-zeros lane value, so that no
+    // condition travels through a scalar register pair.
+    auto load_a = [&](int st, uint32_t (&raw)[MB][G::UPS]) {
+        if constexpr (CW == 1) {
+            // the stage is window row ti = st: taps (st, 0..2), one dword each
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int tj = 0; tj < 3; ++tj) {
+                    const uint32_t keep = static_cast<uint32_t>(-static_cast<int>((a_valid[i] >> (st * 3 + tj)) & 1u));
+                    const uint32_t off = static_cast<uint32_t>(a_base[i] + (st * p.W + tj) * G::D) & keep;
+                    raw[i][tj] = a[off] & keep;
+                }
+        } else {
+            // the stage is round r of tap: W consecutive dwords
+            const int tap = st / G::R, r = st % G::R;
+            const int ti = tap / 3, tj = tap - 3 * ti;
+            const int tap_off = (ti * p.W + tj) * G::D + 2 * G::W * r;
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const uint32_t keep = static_cast<uint32_t>(-static_cast<int>((a_valid[i] >> tap) & 1u));
+                const uint32_t off = static_cast<uint32_t>(a_base[i] + tap_off) & keep;
+                if constexpr (G::W == 4) {
+                    const uint4 x = *reinterpret_cast<const uint4*>(a + off);
+                    raw[i][0] = x.x & keep;
+                    raw[i][1] = x.y & keep;
+                    raw[i][2] = x.z & keep;
+                    raw[i][3] = x.w & keep;
+                } else {
+                    const uint2 x = *reinterpret_cast<const uint2*>(a + off);
+                    raw[i][0] = x.x & keep;
+                    raw[i][1] = x.y & keep;
+                }
+            }
+        }
+    };
+
+    // Weight stage st of channel block nb: CH KB contiguous at ((nblk0 + nb)*STEPS + st*CH) KB.
+    // Thread tid copies UNITS 16-byte pieces; piece index c = tid + 256*k over [nb][CH*64 lanes].
+    auto load_b = [&](int st, v4i (&stage)[G::UNITS]) {
+#pragma unroll
+        for (int k = 0; k < G::UNITS; ++k) {
+            const int c = tid + 256 * k;
+            const int nb = c / (G::CH * 64), rest = c % (G::CH * 64);
+            const int8_t* src = wq + ((static_cast<int64_t>(nblk0 + nb) * G::STEPS + st * G::CH) * 64 + rest) * 16;
+            stage[k] = *reinterpret_cast<const v4i*>(src);
+        }
+    };
+    auto store_b = [&](int buf, const v4i (&stage)[G::UNITS]) {
+#pragma unroll
+        for (int k = 0; k < G::UNITS; ++k)
+            *reinterpret_cast<v4i*>(&lds_b[buf][(tid + 256 * k) * 16]) = stage[k];
+    };
+
+    v16i acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            acc[i][nb] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    uint32_t raw[MB][G::UPS], raw_next[MB][G::UPS];
+    v4i stage[G::UNITS];
+    load_a(0, raw);
+    load_b(0, stage);
+    store_b(0, stage);
+    __syncthreads();
+
+#pragma unroll
+    for (int st = 0; st < G::STAGES; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < G::STAGES) {
+            load_b(st + 1, stage);   // requested before the stage's arithmetic, consumed after it
+            load_a(st + 1, raw_next);
+        }
+#pragma unroll
+        for (int c = 0; c < G::CH; ++c) {
+            const int k = c >> 1, j = c & 1;
+            v4i bf[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                bf[nb] = *reinterpret_cast<const v4i*>(&lds_b[buf][((nb * G::CH + c) * 64 + lane) * 16]);
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const uint32_t xs = j ? (raw[i][k] >> 4) : raw[i][k];
+                v4i af;
+                af.x = static_cast<int>(xs & 0x01010101u);
+                af.y = static_cast<int>(xs & 0x02020202u);
+                af.z = static_cast<int>(xs & 0x04040404u);
+                af.w = static_cast<int>(xs & 0x08080808u);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[i][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nb], acc[i][nb], 0, 0, 0);
+            }
+        }
+        if (st + 1 < G::STAGES) {
+            // buffer buf^1 was last read in stage st-1, which every wavefront has left (barrier)
+            store_b(buf ^ 1, stage);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int k = 0; k < G::UPS; ++k)
+                    raw[i][k] = raw_next[i][k];
+        }
+        __syncthreads();
+    }
+
+    // Accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32]: lanes 0..31 of one
+    // store instruction write 32 consecutive channels (128 bytes) of one pixel.
+    // A row of the tile is a wave-uniform address (scalar arithmetic) plus one per-lane offset
+    // that never changes: channel and the 4h rows of the upper half-wave.
+    char* ybase = reinterpret_cast<char*>(y) + static_cast<size_t>(pix0) * p.Cout * 4;
+    const size_t row_bytes = static_cast<size_t>(p.Cout) * 4;
+    int rows_left = p.total_pix - pix0 - 4 * h;   // MASKED: this lane stores rows below that
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int co = (nblk0 + nb) * 32 + m;
+        const int s_w = sw[co];
+        const uint32_t lane_off = (static_cast<uint32_t>(4 * h) * p.Cout + co) * 4u;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 32 * i + 8 * (v / 4) + (v & 3);   // + 4h, in lane_off
+                const int out = s_w - (acc[i][nb][v] >> 2);
+                char* row_ptr = ybase + row * row_bytes;
+                if constexpr (MASKED)
+                    asm volatile("" : "+v"(rows_left));  // one compare at a time: no hoisted masks
+                if (!MASKED || row < rows_left)
+                    __builtin_nontemporal_store(out, reinterpret_cast<int*>(row_ptr + lane_off));
+            }
+    }
+}
+
+template <int CW, int S, int MB, int NB>
+hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
+                                 const ConvShape& s, hipStream_t stream)
+{
+    const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
+    const int64_t tiles = (total_pix + 128 * MB - 1) / (128 * MB);
+    if (tiles > 0x7fffffff)
+        return hipErrorNotSupported;
+    const MfmaArgs p{s.H, s.W, s.Ho, s.Wo, s.pad, s.Cout, static_cast<int>(total_pix)};
+    const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(s.Cout / (32 * NB)));
+    if (total_pix >= 32 * MB)
+        bconv_mfma_bits_kernel<CW, S, MB, NB, false><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+    else
+        bconv_mfma_bits_kernel<CW, S, MB, NB, true><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+    return hipGetLastError();
+}
+
+template <int CW, int S>
+hipError_t launch_mfma_bits_cw(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
+                               const ConvShape& s, hipStream_t stream)
+{
+    // 64 pixels x 64 channels per wavefront (three or four workgroups resident per CU).  When the
+    // number of such workgroup tiles lies just above three per CU, the launch would end in a
+    // nearly empty second round; wavefronts of 128 pixels halve the tile count and everything is
+    // resident at once (measured at batch 256: 14x14x256->256 26.5 us against 29.3).
+    const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
+    const int64_t small_tiles = ((total_pix + 255) / 256) * (s.Cout / 64);
+    const int64_t cus = device_cu_count();
+    const int mb = option(DABNN_OPT_MFMA_PIXEL_BLOCKS);
+    if (mb == 4 || (mb == 0 && small_tiles > 3 * cus && small_tiles <= 4 * cus))
+        return launch_mfma_bits_inst<CW, S, 4, 2>(a, wq, sw, y, s, stream);
+    return launch_mfma_bits_inst<CW, S, 2, 2>(a, wq, sw, y, s, stream);
+}
+
+}  // namespace
+
+bool bconv_mfma_bits_supports(const ConvShape& s)
+{
+    // whole words (no padding bits inside K), 64-channel tiles, 32-bit dword offsets into the
+    // packed activations and 32-bit byte offsets inside an output tile
+    const int64_t act_dwords = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 2;
+    const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
+    return s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) && s.Cin % 64 == 0 &&
+           (s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8) && s.Cout % 64 == 0 &&
+           act_dwords < (int64_t{1} << 31) && total_pix < (int64_t{1} << 31) && s.Cout <= 8192;
+}
+
+size_t mfma_weights_bytes(const ConvShape& s)
+{
+    return static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw + static_cast<size_t>(s.Cout) * 4;
+}
+
+hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s,
+                                       hipStream_t stream)
+{
+    if (!bconv_mfma_bits_supports(s))
+        return hipErrorNotSupported;
+    const int steps = 18 * s.Cw;
+    const int64_t total = static_cast<int64_t>(s.Cout) * steps * 8;
+    int8_t* q = static_cast<int8_t*>(wq);
+    int32_t* sw = reinterpret_cast<int32_t*>(q + static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw);
+    mfma_prepare_weights_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, stream>>>(
+        reinterpret_cast<const uint32_t*>(w), q, sw, s.Cout, s.Cw, steps);
+    return hipGetLastError();
+}
+
+hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const ConvShape& s,
+                                  hipStream_t stream)
+{
+    if (!bconv_mfma_bits_supports(s))
+        return hipErrorNotSupported;
+    const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
+    const int8_t* q = static_cast<const int8_t*>(wq);
+    const int32_t* sw = reinterpret_cast<const int32_t*>(q + static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw);
+#define DABNN_CASE(CW, S) return launch_mfma_bits_cw<CW, S>(a32, q, sw, y, s, stream)
+    switch (s.Cw * 2 + (s.stride == 2 ? 1 : 0)) {
+        case 2: DABNN_CASE(1, 1);
+        case 3: DABNN_CASE(1, 2);
+        case 4: DABNN_CASE(2, 1);
+        case 5: DABNN_CASE(2, 2);
+        case 8: DABNN_CASE(4, 1);
+        case 9: DABNN_CASE(4, 2);
+        case 16: DABNN_CASE(8, 1);
+        case 17: DABNN_CASE(8, 2);
+        default: return hipErrorNotSupported;
+    }
+#undef DABNN_CASE
+}
+
+}  // namespace dabnn

@@ -117,7 +117,7 @@ def test_options(lib):
     """Options default to 0, are set and read back through the C ABI, and unknown ones are refused;
     the library ignores the environment."""
     import os
-    n_options = 9
+    n_options = 10
     text = open(os.path.join(ROOT, "include", "dabnn.h")).read()
     assert f"DABNN_OPT_COUNT = {n_options}" in text
     for opt in range(n_options):
@@ -217,6 +217,27 @@ def test_int8_route_bad_arguments(lib):
     assert lib.dabnn_bconv2d_int8(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
     assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 80, 64, 3, 3, 1, 1, None) == 4
     assert lib.dabnn_bconv2d_int8(a, w, y, 1, 4, 4, 64, 48, 3, 3, 1, 1, None) == 4
+
+
+def test_mfma_route_bad_arguments_and_buffer_size(lib):
+    """The matrix-core route fed from packed bits: buffer size on the host, and every refusal
+    before any launch."""
+    P = ctypes.c_void_p
+    a, w, y = P(0x10000), P(0x20000), P(0x30000)
+    for Cin, Cout in ((64, 64), (128, 256), (256, 512), (512, 512)):
+        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, 3, 3) == Cout * 9 * Cin + 4 * Cout
+    for Cin, Cout, k in ((80, 64, 3), (192, 64, 3), (64, 32, 3), (64, 64, 1), (0, 64, 3), (64, 16384, 3)):
+        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, k, k) == 0
+    assert lib.dabnn_prepare_weights_mfma(P(0), w, 64, 64, 3, 3, None) == 1
+    assert lib.dabnn_prepare_weights_mfma(a, w, 64, 0, 3, 3, None) == 2
+    assert lib.dabnn_prepare_weights_mfma(a, P(0x20008), 64, 64, 3, 3, None) == 3
+    assert lib.dabnn_prepare_weights_mfma(a, w, 80, 64, 3, 3, None) == 4
+    assert lib.dabnn_bconv2d_mfma(a, w, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
+    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2
+    assert lib.dabnn_bconv2d_mfma(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
+    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 3, 1, None) == 4
+    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 320, 64, 3, 3, 1, 1, None) == 4
+    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 96, 3, 3, 1, 1, None) == 4
 
 
 def test_layout_and_int32_pack_bad_arguments(lib):

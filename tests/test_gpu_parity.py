@@ -572,6 +572,73 @@ def test_int8_matrix_core_route(dabnn, oracle, shape):
     assert torch.equal(out, dabnn.bconv2d(a, wp, Cin, stride, pad))
 
 
+# ------------------------------------------------- matrix cores fed from the packed bits
+MFMA_BITS_SHAPES = [  # N, H, W, Cin, Cout, stride, pad: every word count and stride, ragged pixel counts
+    (3, 13, 11, 64, 64, 1, 1), (2, 9, 9, 64, 128, 2, 1), (2, 10, 7, 128, 128, 1, 1), (2, 9, 9, 128, 256, 2, 1),
+    (3, 7, 7, 256, 256, 1, 1), (2, 8, 8, 256, 512, 2, 1), (2, 7, 7, 512, 512, 1, 1), (1, 12, 12, 512, 64, 2, 1),
+    (5, 14, 14, 64, 192, 1, 0), (2, 11, 13, 128, 64, 1, 2), (4, 9, 9, 256, 128, 2, 0), (2, 8, 9, 512, 128, 1, 2),
+    # fewer pixels than one wavefront tile: the masked kernel
+    (1, 3, 3, 64, 64, 1, 1), (1, 7, 7, 128, 128, 1, 1), (1, 5, 5, 256, 64, 2, 1), (1, 4, 4, 512, 64, 1, 1),
+    (1, 10, 10, 64, 64, 1, 1),   # 100 pixels: whole tiles of 64, masked tiles of 128
+]
+
+
+@pytest.mark.parametrize("blocks", [2, 4])
+@pytest.mark.parametrize("shape", MFMA_BITS_SHAPES, ids=lambda s: "-".join(map(str, s)))
+def test_mfma_route_from_packed_bits(dabnn, oracle, option, shape, blocks):
+    """dabnn_bconv2d_mfma (int8 matrix cores, activation operand expanded from the packed words in
+    the kernel, filters prepared by dabnn_prepare_weights_mfma) against the float oracle, every
+    output, with guard words around the output."""
+    N, H, W, Cin, Cout, stride, pad = shape
+    print("mfma from bits", shape, "pixel blocks", blocks, flush=True)
+    option(dabnn.OPT_MFMA_PIXEL_BLOCKS, blocks)
+    x = wl.activations((N, H, W, Cin), 9100 + sum(shape))
+    wf = wl.weights((Cout, 3, 3, Cin), 9101 + sum(shape), 0.4)
+    a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+    n_bytes = dabnn.mfma_weights_bytes(Cin, Cout)
+    assert n_bytes == Cout * 9 * Cin + 4 * Cout
+    wq = dabnn.prepare_weights_mfma(wp, Cin)
+    want = oracle.bconv2d(x, wf, stride, pad)
+    buf = torch.full((want.size + 512,), -123456789, dtype=torch.int32, device="cuda")
+    out = buf[256:256 + want.size].view(want.shape)
+    dabnn.bconv2d_mfma(a, wq, Cin, Cout, stride, pad, out=out)
+    got = out.cpu().numpy()
+    assert torch.all(buf[:256] == -123456789) and torch.all(buf[-256:] == -123456789)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} of {got.size} outputs differ, first at {bad[0]}: "
+                             f"got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}")
+
+
+def test_mfma_route_full_batch_layers(dabnn, oracle):
+    """The seven layer kinds of the benchmark body at batch 256 through dabnn_bconv2d_mfma, in the
+    launch configuration bench.py times, every output against the oracle."""
+    seen = set()
+    for li, L in enumerate(wl.BIREAL18_BODY):
+        key = (L.H, L.Cin, L.Cout, L.stride)
+        if key in seen:
+            continue
+        seen.add(key)
+        print("mfma from bits, batch 256", key, flush=True)
+        x = wl.activations((256, L.H, L.W, L.Cin), wl.seed_for(5, 100 + li))
+        wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li))
+        a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+        got = dabnn.bconv2d_mfma(a, dabnn.prepare_weights_mfma(wp, L.Cin), L.Cin, L.Cout, L.stride, 1).cpu().numpy()
+        want = oracle.bconv2d(x, wf, L.stride, 1)
+        assert np.array_equal(got, want), key
+        del a, wp, got, want
+
+
+def test_mfma_route_refuses_what_it_does_not_cover(dabnn):
+    assert dabnn.mfma_weights_bytes(80, 64) == 0 and dabnn.mfma_weights_bytes(64, 48) == 0
+    assert dabnn.mfma_weights_bytes(192, 64) == 0 and dabnn.mfma_weights_bytes(64, 64, 5, 5) == 0
+    a = torch.zeros((1, 6, 6, 1), dtype=torch.int64, device="cuda")
+    wq = torch.zeros((64 * 9 * 64 + 256,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(dabnn.DabnnError) as e:
+        dabnn.bconv2d_mfma(a, wq, 64, 64, 3, 1)     # stride 3
+    assert e.value.status == 4
+
+
 def test_int8_route_refuses_other_channel_counts(dabnn):
     a8 = torch.ones((1, 4, 4, 80), dtype=torch.int8, device="cuda")
     w8 = torch.ones((64, 3, 3, 80), dtype=torch.int8, device="cuda")
