@@ -188,6 +188,31 @@ def main():
     pack_med, pack_min = np.median(pack_us, axis=0), pack_us.min(axis=0)
     conv_med, conv_min = np.median(conv_us, axis=0), conv_us.min(axis=0)
 
+    # ---- the same launches without an event between them: the 16 bit-packs of a step back to
+    # back, S times, between one pair of events; then the 16 convolutions likewise.  An event
+    # interval of the sampling pass contains the event's own dispatch (1-2 us per launch); these
+    # two figures do not, and are what the kernel durations of a rocprofv3 trace add up to.
+    def pass_us(launch_all):
+        launch_all()
+        torch.cuda.synchronize()
+        e0, e1 = event(), event()
+        e0.record()
+        for _ in range(S):
+            launch_all()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / S
+
+    def all_packs():
+        for li in range(len(layers)):
+            binding.bitpack(xs[li], out=acts[li])
+
+    def all_convs():
+        for li, L in enumerate(layers):
+            binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li])
+    pack_pass = pass_us(all_packs)
+    conv_pass = pass_us(all_convs)
+
     ops = [L.ops(N) for L in layers]
     total_ops = float(sum(ops))
     pack_bytes = [xs[li].numel() * 4 + acts[li].numel() * 8 for li in range(len(layers))]
@@ -238,6 +263,10 @@ def main():
             "frac": round(conv_tops / VALU_PEAK_TOPS, 4),
             "frac_from_minimum_intervals": round(total_ops / (conv_min.sum() * 1e-6) / 1e12 / VALU_PEAK_TOPS, 4),
             "samples_per_launch": S,
+            "back_to_back": {"what": f"the 16 conv launches of a step with no event between them, {S} times",
+                             "us_per_step": round(conv_pass, 1),
+                             "achieved": round(total_ops / (conv_pass * 1e-6) / 1e12, 2),
+                             "frac": round(total_ops / (conv_pass * 1e-6) / 1e12 / VALU_PEAK_TOPS, 4)},
             "traffic": MEASURED_TRAFFIC_B256["bconv"] if N == 256 else None,
             "traffic_note": "HBM bytes per step over the 16 conv launches (algorithmic 1.597e9)",
         },
@@ -249,6 +278,10 @@ def main():
             "unit": "GB/s",
             "frac": round(pack_gbps / HBM_PEAK_GBPS, 4),
             "samples_per_launch": S,
+            "back_to_back": {"what": f"the 16 bit-pack launches of a step with no event between them, {S} times",
+                             "us_per_step": round(pack_pass, 1),
+                             "achieved": round(sum(pack_bytes) / (pack_pass * 1e-6) / 1e9, 1),
+                             "frac": round(sum(pack_bytes) / (pack_pass * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
             "traffic": MEASURED_TRAFFIC_B256["bitpack"] if N == 256 else None,
             "traffic_note": "HBM bytes per step over the 16 bit-pack launches (algorithmic 1.775e9)",
         },
