@@ -813,13 +813,16 @@ def test_hip_graph_replay_of_the_hot_path(dabnn, oracle):
     a = torch.empty((N, H, W, Cin // 64), dtype=torch.int64, device="cuda")
     y = torch.empty((N, H, W, Cout), dtype=torch.int32, device="cuda")
     y0 = torch.empty_like(y)
+    ym = torch.empty_like(y)
     bits = torch.empty((N, H, W, Cout // 64), dtype=torch.int64, device="cuda")
+    wq = dabnn.prepare_weights_mfma(wp, Cin)
 
     def enqueue():
         dabnn.bitpack(xg, out=a)
         dabnn.bconv2d(a, wp, Cin, 1, 1, out=y)
         dabnn.bconv2d_zeropad(a, wp, Cin, 1, 1, out=y0)
         dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, 1, 1, out=bits)
+        dabnn.bconv2d_mfma(a, wq, Cin, Cout, 1, 1, out=ym)
 
     xg.copy_(gpu(wl.activations((N, H, W, Cin), 4200)))
     enqueue()  # eager once: one-time occupancy queries happen outside the capture
@@ -830,12 +833,13 @@ def test_hip_graph_replay_of_the_hot_path(dabnn, oracle):
     for rep in range(4):
         x = wl.activations((N, H, W, Cin), 4210 + rep)
         xg.copy_(gpu(x))          # eager work between the replays
-        y.zero_(); y0.zero_(); bits.zero_()
+        y.zero_(); y0.zero_(); bits.zero_(); ym.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(words(a), oracle.bitpack(x)), rep
         assert np.array_equal(y.cpu().numpy(), oracle.bconv2d(x, wf, 1, 1)), rep
+        assert np.array_equal(ym.cpu().numpy(), oracle.bconv2d(x, wf, 1, 1)), rep
         assert np.array_equal(y0.cpu().numpy(), oracle.bconv2d_zeropad(x, wf, 1, 1)), rep
         assert np.array_equal(words(bits), oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, 1, 1)), rep
 
