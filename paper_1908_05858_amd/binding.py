@@ -316,7 +316,9 @@ def mfma_weights_bytes(Cin, Cout, kh=3, kw=3):
 def prepare_weights_mfma(w, Cin, out=None):
     """Packed filters int64 [Cout, 3, 3, Cin/64] -> the uint8 buffer dabnn_bconv2d_mfma consumes
     (int8 operands in kernel order followed by one int32 constant per output channel)."""
-    Cout, kh, kw, _ = w.shape
+    Cout, kh, kw, words = w.shape
+    if words * 64 != Cin:
+        raise ValueError("packed word count does not match Cin")
     n = mfma_weights_bytes(Cin, Cout, kh, kw)
     if n == 0:
         raise DabnnError(4, "dabnn_mfma_weights_bytes")
@@ -330,7 +332,11 @@ def prepare_weights_mfma(w, Cin, out=None):
 def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None):
     """a: packed int64 [N,H,W,Cin/64]; wq: prepare_weights_mfma of the layer's 3x3 filters ->
     int32 [N,Ho,Wo,Cout], the values of bconv2d, computed on the int8 matrix cores."""
-    N, H, W, _ = a.shape
+    N, H, W, words = a.shape
+    if words * 64 != Cin:
+        raise ValueError("packed word count does not match Cin")
+    if wq.numel() != mfma_weights_bytes(Cin, Cout):
+        raise ValueError("wq is not the prepared filter buffer of this layer shape")
     Ho, Wo = conv_out_dim(H, 3, stride, pad), conv_out_dim(W, 3, stride, pad)
     if Ho <= 0 or Wo <= 0:
         raise DabnnError(2, "dabnn_bconv2d_mfma")

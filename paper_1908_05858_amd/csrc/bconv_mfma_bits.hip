@@ -319,12 +319,13 @@ hipError_t launch_mfma_bits_cw(const uint32_t* a, const int8_t* wq, const int32_
 bool bconv_mfma_bits_supports(const ConvShape& s)
 {
     // whole words (no padding bits inside K), 64-channel tiles, 32-bit dword offsets into the
-    // packed activations and 32-bit byte offsets inside an output tile
+    // packed activations, 32-bit pixel indices up to a rounded-up grid, and 32-bit byte offsets
+    // inside an output tile
     const int64_t act_dwords = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 2;
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     return s.kh == 3 && s.kw == 3 && (s.stride == 1 || s.stride == 2) && s.Cin % 64 == 0 &&
            (s.Cw == 1 || s.Cw == 2 || s.Cw == 4 || s.Cw == 8) && s.Cout % 64 == 0 &&
-           act_dwords < (int64_t{1} << 31) && total_pix < (int64_t{1} << 31) && s.Cout <= 8192;
+           act_dwords < (int64_t{1} << 31) && total_pix < (int64_t{1} << 31) - 4096 && s.Cout <= 8192;
 }
 
 size_t mfma_weights_bytes(const ConvShape& s)
