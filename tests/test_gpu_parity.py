@@ -257,8 +257,12 @@ def run_conv(dabnn, oracle, N, H, W, Cin, Cout, k, stride, pad, seed, algo, p_pl
     try:
         dabnn.bconv2d(a, wp, Cin, stride, pad, out=out, algo=algo)
     except dabnn.DabnnError as e:
+        # a forced family may refuse a shape it does not cover: then it must leave the output
+        # alone, and the automatic choice must be another family
         if e.status == 4 and algo in (2, 3):
-            pytest.skip("this kernel family does not cover the shape")
+            assert torch.all(buf == -123456789)
+            assert dabnn.pick_algo(N, H, W, Cin, Cout, k, k, stride, pad) != algo
+            return
         raise
     want = oracle.bconv2d(x, wf, stride, pad)
     got = out.cpu().numpy()
