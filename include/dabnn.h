@@ -86,7 +86,8 @@ typedef enum {
     DABNN_OPT_BITPACK_ROWWISE = 6, /* 1: the row-wise kernel for channel counts that are no multiple of 64 */
     DABNN_OPT_AREG_SPLIT = 7,      /* DABNN_ALGO_AREG kernels in which the four wavefronts of a workgroup share a
                                       channel group (always used above 8 words per pixel, by default at 8 when
-                                      Cout % 16 == 0): 1 not below 9 words, 4 also at 4 words */
+                                      Cout % 16 == 0 and the launch has 3 or more groups per CU): 1 not below 9
+                                      words, 4 also at 4 words, 8 at 8 words whatever the launch's size */
     DABNN_OPT_AREG_RANGES_PER_SIMD = 8, /* n > 0: cut the work of a DABNN_ALGO_AREG launch into n ranges per SIMD */
     DABNN_OPT_MFMA_PIXEL_BLOCKS = 9, /* dabnn_bconv2d_mfma: 2 or 4 blocks of 32 pixels per wavefront */
     DABNN_OPT_COUNT = 10

@@ -122,7 +122,13 @@ hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, c
     // Option DABNN_OPT_AREG_SPLIT: 4 forces it for 4 words as well, 1 never uses it below 9 words.
     const int split_option = option(DABNN_OPT_AREG_SPLIT);
     const bool split_fits = s.Cw % 4 == 0 && s.Cout % 16 == 0 && option(DABNN_OPT_AREG_STORE) != 1;
-    const bool use_split = s.Cw > 8 || (split_fits && split_option != 1 && (s.Cw == 8 || split_option == 4));
+    // A latency-bound launch at 8 words (fewer than 3 groups per CU) is shorter with the
+    // one-wavefront kernel's groups of 4 channels: 7x7x512->512 at batch 1 6.8 against 8.1 us, at
+    // batch 24 11.7 against 13.9, at batch 32 13.7 against 13.0.
+    const int64_t tiles = (static_cast<int64_t>(s.N) * s.Ho * s.Wo + 63) / 64;
+    const bool few_groups = tiles * (s.Cout / 16) < 3 * static_cast<int64_t>(device_cu_count());
+    const bool use_split = s.Cw > 8 || (split_fits && split_option != 1 &&
+                                        ((s.Cw == 8 && (!few_groups || split_option == 8)) || split_option == 4));
     if (!use_split) {
 #define DABNN_CASE(CW, S) return launch_areg_cw##CW##_s##S(a32, w32, y, s, stream)
         DABNN_SWITCH_CW_S(s, DABNN_CASE)

@@ -338,12 +338,13 @@ def test_odd_shapes_tuned(dabnn, oracle, shape, algo):
 
 
 @pytest.mark.parametrize("env", [("OPT_AREG_STORE", 1, 3), ("OPT_AREG_STORE", 16, 3), ("OPT_AREG_SPLIT", 4, 3),
-                                 ("OPT_WREG_PIXELS", 7, 2), ("OPT_WREG_PIXELS", 8, 2)],
+                                 ("OPT_AREG_SPLIT", 8, 3), ("OPT_WREG_PIXELS", 7, 2), ("OPT_WREG_PIXELS", 8, 2)],
                          ids=lambda e: f"{e[0]}={e[1]}")
 def test_kernel_variants(dabnn, oracle, env, option):
     """Both store variants of the activation-stationary family, its four-wavefront kernels at 4
     and 8 words per pixel, and both chunk widths of the filter-stationary family, forced through
-    the library's options."""
+    the library's options (launches as small as these take the direct store and the one-wavefront
+    kernel by default)."""
     name, value, algo = env
     option(getattr(dabnn, name), value)
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
@@ -360,6 +361,8 @@ def test_work_split_and_remainder_pieces(dabnn, oracle, slots, tail, option):
     groups or as direct-store pieces; the four-wavefront kernels split over workgroups alike."""
     option(dabnn.OPT_AREG_SLOTS, slots)
     option(dabnn.OPT_AREG_TAIL, tail)
+    option(dabnn.OPT_AREG_STORE, 16)   # the transposed store and the four-wavefront kernel at 8
+    option(dabnn.OPT_AREG_SPLIT, 8)    # words, which launches this small would not take by default
     for shape in [(2, 14, 14, 64, 64, 3, 1, 1), (3, 28, 28, 128, 128, 3, 2, 1), (2, 9, 13, 256, 96, 3, 1, 1),
                   (1, 23, 17, 64, 48, 3, 1, 1), (2, 7, 7, 512, 64, 3, 1, 1), (2, 9, 7, 320, 48, 3, 1, 1),
                   (2, 6, 5, 1024, 32, 3, 1, 1), (1, 9, 9, 704, 32, 3, 2, 1)]:
