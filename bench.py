@@ -552,45 +552,55 @@ def widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps,
         }
         del w8s, a8s
 
-    # Second comparison row: the int8 matrix cores fed from the PACKED activations
+    # Second comparison row: the matrix cores fed from the PACKED activations
     # (dabnn_bconv2d_mfma; only the filters are expanded, ahead of time like they are packed ahead
-    # of time).  The step is the headline step with dabnn_bconv2d replaced by it; per layer, HIP
-    # event intervals of the same launches beside those of the XOR/popcount kernel.
+    # of time), with int8 and with FP4 operands.  The step is the headline step with dabnn_bconv2d
+    # replaced by it; per layer, HIP event intervals of the same launches beside those of the
+    # XOR/popcount kernel.
     if all(binding.mfma_weights_bytes(L.Cin, L.Cout) > 0 for L in layers):
-        wqs = [binding.prepare_weights_mfma(wps[li], L.Cin) for li, L in enumerate(layers)]
+        peaks = {"int8": 5.0e15, "fp4": 10.1e15}
+        per_format = {}
+        for name, fmt in (("int8", binding.MFMA_INT8), ("fp4", binding.MFMA_FP4)):
+            wqs = [binding.prepare_weights_mfma(wps[li], L.Cin, fmt=fmt) for li, L in enumerate(layers)]
 
-        def bits_step(conv_only=False):
+            def bits_step(conv_only=False):
+                for li, L in enumerate(layers):
+                    if not conv_only:
+                        binding.bitpack(xs[li], out=acts[li])
+                    binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1, out=ys[li], fmt=fmt)
+            bits_ms = wall_ms(bits_step, reps)
+            bits_conv_ms = wall_ms(lambda: bits_step(conv_only=True), reps)
+            rows, seen = [], set()
             for li, L in enumerate(layers):
-                if not conv_only:
-                    binding.bitpack(xs[li], out=acts[li])
-                binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1, out=ys[li])
-        bits_ms = wall_ms(bits_step, reps)
-        bits_conv_ms = wall_ms(lambda: bits_step(conv_only=True), reps)
-        rows, seen = [], set()
-        for li, L in enumerate(layers):
-            key = (L.H, L.Cin, L.Cout, L.stride)
-            if key in seen:
-                continue
-            seen.add(key)
-            t_mfma, _ = launch_us(lambda: binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1, out=ys[li]))
-            t_valu, _ = launch_us(lambda: binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li]))
-            rows.append({"layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}", "mfma_us": round(t_mfma, 2),
-                         "mfma_frac_of_int8_peak": round(L.ops(N) / t_mfma / 1e6 / 5000.0, 4),
-                         "xor_popcount_us": round(t_valu, 2)})
+                key = (L.H, L.Cin, L.Cout, L.stride)
+                if key in seen:
+                    continue
+                seen.add(key)
+                t_mfma, _ = launch_us(lambda: binding.bconv2d_mfma(acts[li], wqs[li], L.Cin, L.Cout, L.stride, 1,
+                                                                    out=ys[li], fmt=fmt))
+                t_valu, _ = launch_us(lambda: binding.bconv2d(acts[li], wps[li], L.Cin, L.stride, 1, out=ys[li]))
+                rows.append({"layer": f"{L.H}x{L.W}x{L.Cin}->{L.Cout}s{L.stride}", "mfma_us": round(t_mfma, 2),
+                             "mfma_frac_of_peak": round(L.ops(N) / (t_mfma * 1e-6) / peaks[name], 4),
+                             "xor_popcount_us": round(t_valu, 2)})
+            per_format[name] = {
+                "ms_per_step": round(bits_ms, 4),
+                "GOPS": round(total_ops / (bits_ms * 1e-3) / 1e9, 1),
+                "conv_only_ms_per_step": round(bits_conv_ms, 4),
+                "conv_only_GOPS": round(total_ops / (bits_conv_ms * 1e-3) / 1e9, 1),
+                "conv_only_frac_of_mfma_peak": round(total_ops / (bits_conv_ms * 1e-3) / peaks[name], 4),
+                "mfma_peak_TOPs": peaks[name] / 1e12,
+                "per_layer": rows,
+            }
+            del wqs
         result["mfma_from_packed_bits_comparison"] = {
-            "what": "the headline step with dabnn_bconv2d replaced by dabnn_bconv2d_mfma: int8 "
-                    "v_mfma_i32_32x32x32_i8 whose activation operand is expanded from the packed "
-                    "words inside the kernel (one AND per operand register) and whose filters are "
-                    "prepared once per model; same int32 outputs.  A comparison, not the method's "
-                    "path: the headline stays XOR + popcount",
-            "ms_per_step": round(bits_ms, 4),
-            "GOPS": round(total_ops / (bits_ms * 1e-3) / 1e9, 1),
-            "conv_only_ms_per_step": round(bits_conv_ms, 4),
-            "conv_only_GOPS": round(total_ops / (bits_conv_ms * 1e-3) / 1e9, 1),
-            "conv_only_frac_of_int8_mfma_peak": round(total_ops / (bits_conv_ms * 1e-3) / 5.0e15, 4),
-            "per_layer": rows,
+            "what": "the headline step with dabnn_bconv2d replaced by dabnn_bconv2d_mfma: matrix "
+                    "instructions (int8 v_mfma_i32_32x32x32_i8, or FP4 v_mfma_scale_f32_32x32x64_f8f6f4) "
+                    "whose activation operand is expanded from the packed words inside the kernel "
+                    "(one AND per operand register) and whose filters are prepared once per model; "
+                    "same int32 outputs.  A comparison, not the method's path: the headline stays "
+                    "XOR + popcount",
+            **per_format,
         }
-        del wqs
 
 
 if __name__ == "__main__":

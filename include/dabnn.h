@@ -252,31 +252,35 @@ int dabnn_bconv2d_int8(const int8_t *a8, const int8_t *w8, int32_t *y, int N, in
                        int Cout, int kh, int kw, int stride, int pad, void *stream);
 
 /*
- * Matrix-core route fed from the packed bits.  The same integers as dabnn_bconv2d (Sec. 2.1.2,
- * Eq. 6-7), computed as an int8 matrix product: with a = 1 for an activation of -1 (else 0) and
+* Matrix-core route fed from the packed bits.  The same integers as dabnn_bconv2d (Sec. 2.1.2,
+ * Eq. 6-7), computed as a matrix product: with a = 1 for an activation of -1 (else 0) and
  * s = +-1 for the weights, y = sum_k (1 - 2 a_k) s_k = S - 2 * sum_k a_k s_k, S = sum_k s_k.  The
  * activation operand is expanded from the packed words inside the kernel (one AND per operand
  * register), so the activations stay packed in memory; only the filters are expanded, once per
- * model, into the order in which the kernel consumes them.
+ * model, into the order in which the kernel consumes them.  `format` chooses the matrix
+ * instruction: DABNN_MFMA_INT8 (v_mfma_i32_32x32x32_i8, one byte per weight) or DABNN_MFMA_FP4
+ * (v_mfma_scale_f32_32x32x64_f8f6f4 on 4-bit E2M1 operands, one nibble per weight, fp32
+ * accumulation of exact integers); a prepared buffer is used with the format it was made for.
  *
  * dabnn_mfma_weights_bytes: size in bytes of the prepared filter buffer for a layer, 0 if the
- *   shape is outside what this route supports.
+ *   shape or the format is outside what this route supports.
  * dabnn_prepare_weights_mfma:
  *   w  : u64 [Cout][3][3][Cin/64]  device, as written by dabnn_pack_weights
  *   wq : dabnn_mfma_weights_bytes(...) bytes, device, 16-byte aligned, written completely
- *        (int8 operands in kernel order, then S[Cout] as int32); owned by the caller.
+ *        (operands in kernel order, then S[Cout] as int32); owned by the caller.
  * dabnn_bconv2d_mfma:
  *   a  : u64 [N][H][W][Cin/64]     device, as written by dabnn_bitpack
- *   wq : the prepared filters of the same layer shape
+ *   wq : the prepared filters of the same layer shape and format
  *   y  : i32 [N][Ho][Wo][Cout]     device, written completely.  Out-of-image taps count as +1.
  * Supported: 3x3 kernels, stride 1 or 2, Cin in {64, 128, 256, 512}, Cout % 64 == 0 and at most
  * 8192, packed activations below 2^31 dwords; DABNN_ERR_UNSUPPORTED otherwise (nothing launched).
  */
-size_t dabnn_mfma_weights_bytes(int Cin, int Cout, int kh, int kw);
+typedef enum { DABNN_MFMA_INT8 = 0, DABNN_MFMA_FP4 = 1 } dabnn_mfma_format;
+size_t dabnn_mfma_weights_bytes(int Cin, int Cout, int kh, int kw, int format);
 int dabnn_prepare_weights_mfma(const uint64_t *w, void *wq, int Cin, int Cout, int kh, int kw,
-                               void *stream);
+                               int format, void *stream);
 int dabnn_bconv2d_mfma(const uint64_t *a, const void *wq, int32_t *y, int N, int H, int W, int Cin,
-                       int Cout, int kh, int kw, int stride, int pad, void *stream);
+                       int Cout, int kh, int kw, int stride, int pad, int format, void *stream);
 
 /*
  * Binary convolution with ZERO padding.  The paper builds its binary convolution on the standard

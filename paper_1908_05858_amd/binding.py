@@ -49,9 +49,9 @@ def load():
     lib.dabnn_bconv2d_bn_residual.restype = i32
     lib.dabnn_expand_int8.argtypes, lib.dabnn_expand_int8.restype = [vp, vp, i64, i32, vp], i32
     lib.dabnn_bconv2d_int8.argtypes, lib.dabnn_bconv2d_int8.restype = [vp] * 3 + [i32] * 9 + [vp], i32
-    lib.dabnn_mfma_weights_bytes.argtypes, lib.dabnn_mfma_weights_bytes.restype = [i32] * 4, ctypes.c_size_t
-    lib.dabnn_prepare_weights_mfma.argtypes, lib.dabnn_prepare_weights_mfma.restype = [vp, vp] + [i32] * 4 + [vp], i32
-    lib.dabnn_bconv2d_mfma.argtypes, lib.dabnn_bconv2d_mfma.restype = [vp] * 3 + [i32] * 9 + [vp], i32
+    lib.dabnn_mfma_weights_bytes.argtypes, lib.dabnn_mfma_weights_bytes.restype = [i32] * 5, ctypes.c_size_t
+    lib.dabnn_prepare_weights_mfma.argtypes, lib.dabnn_prepare_weights_mfma.restype = [vp, vp] + [i32] * 5 + [vp], i32
+    lib.dabnn_bconv2d_mfma.argtypes, lib.dabnn_bconv2d_mfma.restype = [vp] * 3 + [i32] * 10 + [vp], i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
@@ -308,35 +308,38 @@ def bconv2d_int8(a8, w8, stride=1, pad=0, out=None):
     return out
 
 
-def mfma_weights_bytes(Cin, Cout, kh=3, kw=3):
+MFMA_INT8, MFMA_FP4 = 0, 1
+
+
+def mfma_weights_bytes(Cin, Cout, kh=3, kw=3, fmt=MFMA_INT8):
     """Bytes of the prepared filter buffer of dabnn_bconv2d_mfma; 0 for an unsupported layer."""
-    return load().dabnn_mfma_weights_bytes(Cin, Cout, kh, kw)
+    return load().dabnn_mfma_weights_bytes(Cin, Cout, kh, kw, fmt)
 
 
-def prepare_weights_mfma(w, Cin, out=None):
+def prepare_weights_mfma(w, Cin, out=None, fmt=MFMA_INT8):
     """Packed filters int64 [Cout, 3, 3, Cin/64] -> the uint8 buffer dabnn_bconv2d_mfma consumes
-    (int8 operands in kernel order followed by one int32 constant per output channel)."""
+    (operands in kernel order, int8 or FP4, followed by one int32 constant per output channel)."""
     Cout, kh, kw, words = w.shape
     if words * 64 != Cin:
         raise ValueError("packed word count does not match Cin")
-    n = mfma_weights_bytes(Cin, Cout, kh, kw)
+    n = mfma_weights_bytes(Cin, Cout, kh, kw, fmt)
     if n == 0:
         raise DabnnError(4, "dabnn_mfma_weights_bytes")
     if out is None:
         out = torch.empty((n,), dtype=torch.uint8, device=w.device)
     _check(load().dabnn_prepare_weights_mfma(_dev(w, torch.int64, "w"), _dev(out, torch.uint8, "out"),
-                                             Cin, Cout, kh, kw, _stream()), "dabnn_prepare_weights_mfma")
+                                             Cin, Cout, kh, kw, fmt, _stream()), "dabnn_prepare_weights_mfma")
     return out
 
 
-def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None):
-    """a: packed int64 [N,H,W,Cin/64]; wq: prepare_weights_mfma of the layer's 3x3 filters ->
-    int32 [N,Ho,Wo,Cout], the values of bconv2d, computed on the int8 matrix cores."""
+def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None, fmt=MFMA_INT8):
+    """a: packed int64 [N,H,W,Cin/64]; wq: prepare_weights_mfma of the layer's 3x3 filters in the
+    same format -> int32 [N,Ho,Wo,Cout], the values of bconv2d, computed on the matrix cores."""
     N, H, W, words = a.shape
     if words * 64 != Cin:
         raise ValueError("packed word count does not match Cin")
-    if wq.numel() != mfma_weights_bytes(Cin, Cout):
-        raise ValueError("wq is not the prepared filter buffer of this layer shape")
+    if wq.numel() != mfma_weights_bytes(Cin, Cout, 3, 3, fmt):
+        raise ValueError("wq is not the prepared filter buffer of this layer shape and format")
     Ho, Wo = conv_out_dim(H, 3, stride, pad), conv_out_dim(W, 3, stride, pad)
     if Ho <= 0 or Wo <= 0:
         raise DabnnError(2, "dabnn_bconv2d_mfma")
@@ -344,7 +347,7 @@ def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None):
         out = torch.empty((N, Ho, Wo, Cout), dtype=torch.int32, device=a.device)
     _check(load().dabnn_bconv2d_mfma(_dev(a, torch.int64, "a"), _dev(wq, torch.uint8, "wq"),
                                      _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, 3, 3, stride, pad,
-                                     _stream()), "dabnn_bconv2d_mfma")
+                                     fmt, _stream()), "dabnn_bconv2d_mfma")
     return out
 
 

@@ -14,7 +14,14 @@
 // (dabnn_prepare_weights_mfma): byte (h, v, b) of a step is s * 2^(3 - v), so every product is
 // +-8 a and the accumulator holds 8 * sum a s; y = S - acc / 4.
 //
-//   mfma_prepare_weights_kernel : packed filters -> [Cout/32][steps][64 lanes][16 B] int8, S[Cout]
+// FP4 mode (v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in the 4-bit E2M1 format, scales
+// 1.0): twice the products per instruction.  One 32-bit word x per lane is one whole operand: the
+// registers are x & 0x11111111 (bit 4k as the value 0.5 in nibble k), x & 0x22222222 (bit 4k+1 as
+// 1.0), x & 0x44444444 (bit 4k+2 as 2.0) and (x >> 3) & 0x11111111 (bit 4k+3 as 0.5); the prepared
+// weights are s * 2, s * 1, s * 0.5, s * 2 in the same places, so every product is +-a exactly and
+// the fp32 accumulator holds the integer sum a s; y = S - 2 acc.
+//
+//   mfma_prepare_weights_kernel : packed filters -> [Cout/32][steps][64 lanes][16 B], S[Cout]
 //   bconv_mfma_bits_kernel      : a wavefront owns 32*MB pixels x 32*NB channels (MB x NB
 //       v_mfma_i32_32x32x32_i8 accumulators); the four wavefronts of a workgroup own different
 //       pixels and the same channels, and share the weight operands through LDS (double-buffered
@@ -32,7 +39,9 @@ namespace dabnn {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 // Order of the K dimension, shared by the two kernels.  A pixel's tap holds 2*CW dwords.  They are
 // consumed in R rounds of 2*W dwords; in a round the lanes of half h take dwords 2W*r + W*h + q,
@@ -40,6 +49,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 __host__ __device__ constexpr int mfma_w(int cw) { return cw < 4 ? cw : 4; }
 
 // One thread per (output channel, step, half, register): 4 bytes out.
+template <bool FP4>
 __global__ __launch_bounds__(256) void mfma_prepare_weights_kernel(
     const uint32_t* __restrict__ wp, int8_t* __restrict__ wq, int32_t* __restrict__ sw, int Cout,
     int Cw, int steps)
@@ -53,17 +63,26 @@ __global__ __launch_bounds__(256) void mfma_prepare_weights_kernel(
         const int64_t ct = idx >> 3;
         const int t = static_cast<int>(ct % steps);
         const int n = static_cast<int>(ct / steps);
-        const int j = t & 1;
-        const int u = t >> 1;  // (tap*R + r)*W + q
+        const int j = FP4 ? 0 : (t & 1);
+        const int u = FP4 ? t : (t >> 1);  // (tap*R + r)*W + q
         const int q = u % W;
         const int r = (u / W) % R;
         const int tap = u / (W * R);
         const uint32_t x = wp[(static_cast<int64_t>(n) * 9 + tap) * D + 2 * W * r + W * h + q];
         uint32_t out = 0;
+        if (FP4) {
+            // E2M1: 0.5 = 0001, 1.0 = 0010, 2.0 = 0100, sign = 1000
+            const uint32_t magnitude = v == 1 ? 0x2u : (v == 2 ? 0x1u : 0x4u);
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t bit = (x >> (4 * k + v)) & 1u;
+                out |= (magnitude | (bit ? 0x8u : 0u)) << (4 * k);
+            }
+        } else {
         for (int b = 0; b < 4; ++b) {
             const uint32_t bit = (x >> (4 * j + v + 8 * b)) & 1u;
             const int val = (bit ? -1 : 1) * (8 >> v);
             out |= (static_cast<uint32_t>(val) & 0xffu) << (8 * b);
+        }
         }
         // [n/32][t][lane = 32h + n%32][16 bytes = 4 registers]
         const int64_t o = ((static_cast<int64_t>(n >> 5) * steps + t) * 64 + 32 * h + (n & 31)) * 16 + 4 * v;
@@ -83,33 +102,36 @@ struct MfmaArgs {
     int H, W, Ho, Wo, pad, Cout, total_pix;
 };
 
-template <int CW, int S, int MB, int NB>
+template <int CW, int MB, int NB, bool FP4>
 struct MfmaGeom {
     static constexpr int W = mfma_w(CW);
     static constexpr int R = CW / W;
     static constexpr int D = 2 * CW;
-    static constexpr int STEPS = 18 * CW;
-    // steps per LDS stage: three taps (a window row) at one word per pixel, otherwise one round
-    static constexpr int CH = CW == 1 ? 6 : 2 * W;
+    static constexpr int SPD = FP4 ? 1 : 2;            // matrix instructions (steps) per dword
+    static constexpr int STEPS = 9 * CW * SPD;
+    // dwords a lane consumes per LDS stage: three taps (a window row) at one word per pixel,
+    // otherwise one round
+    static constexpr int UPS = CW == 1 ? 3 : W;
+    static constexpr int CH = UPS * SPD;               // steps per stage
     static constexpr int STAGES = STEPS / CH;
-    static constexpr int UPS = CH / 2;                 // dwords a lane consumes per stage
     static constexpr int STAGE_BYTES = CH * NB * 1024;
-    static constexpr int UNITS = STAGE_BYTES / 16 / 256;  // 16-byte copies per thread and stage
-    static_assert(STEPS % CH == 0 && STAGE_BYTES % (16 * 256) == 0, "stage geometry");
+    static constexpr int PIECES = STAGE_BYTES / 16;    // 16-byte copies per stage
+    static constexpr int UNITS = (PIECES + 255) / 256; // ... per thread (the last one may be partial)
+    static_assert(STEPS % CH == 0 && PIECES % 64 == 0, "stage geometry");
 };
 
 // MASKED = false: the tensor has at least 32*MB pixels, and a wavefront whose tile would reach
 // past the end computes the LAST 32*MB pixels instead (some of them a second time, with the same
 // results), so that no load or store needs a bounds check.  MASKED = true: fewer pixels than one
 // tile; rows past the end repeat the last pixel and are not stored.
-template <int CW, int S, int MB, int NB, bool MASKED>
+template <int CW, int S, int MB, int NB, bool MASKED, bool FP4>
 __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __restrict__ a,
                                                               const int8_t* __restrict__ wq,
                                                               const int32_t* __restrict__ sw,
                                                               int32_t* __restrict__ y,
                                                               const MfmaArgs p)
 {
-    using G = MfmaGeom<CW, S, MB, NB>;
+    using G = MfmaGeom<CW, MB, NB, FP4>;
     __shared__ __attribute__((aligned(16))) int8_t lds_b[2][G::STAGE_BYTES];
 
     const int tid = threadIdx.x;
@@ -189,6 +211,8 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
         for (int k = 0; k < G::UNITS; ++k) {
             const int c = tid + 256 * k;
+            if (256 * (k + 1) > G::PIECES && c >= G::PIECES)   // partial last unit (whole wavefronts)
+                continue;
             const int nb = c / (G::CH * 64), rest = c % (G::CH * 64);
             const int8_t* src = wq + ((static_cast<int64_t>(nblk0 + nb) * G::STEPS + st * G::CH) * 64 + rest) * 16;
             stage[k] = *reinterpret_cast<const v4i*>(src);
@@ -197,15 +221,19 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
     auto store_b = [&](int buf, const v4i (&stage)[G::UNITS]) {
 #pragma unroll
         for (int k = 0; k < G::UNITS; ++k)
-            *reinterpret_cast<v4i*>(&lds_b[buf][(tid + 256 * k) * 16]) = stage[k];
+            if (256 * (k + 1) <= G::PIECES || tid + 256 * k < G::PIECES)
+                *reinterpret_cast<v4i*>(&lds_b[buf][(tid + 256 * k) * 16]) = stage[k];
     };
 
-    v16i acc[MB][NB];
+    using acc_t = std::conditional_t<FP4, v16f, v16i>;
+    acc_t acc[MB][NB];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-            acc[i][nb] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[i][nb][v] = 0;
 
     uint32_t raw[MB][G::UPS], raw_next[MB][G::UPS];
     v4i stage[G::UNITS];
@@ -223,22 +251,35 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
         }
 #pragma unroll
         for (int c = 0; c < G::CH; ++c) {
-            const int k = c >> 1, j = c & 1;
+            const int k = c / G::SPD, j = c % G::SPD;
             v4i bf[NB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
                 bf[nb] = *reinterpret_cast<const v4i*>(&lds_b[buf][((nb * G::CH + c) * 64 + lane) * 16]);
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
-                const uint32_t xs = j ? (raw[i][k] >> 4) : raw[i][k];
-                v4i af;
-                af.x = static_cast<int>(xs & 0x01010101u);
-                af.y = static_cast<int>(xs & 0x02020202u);
-                af.z = static_cast<int>(xs & 0x04040404u);
-                af.w = static_cast<int>(xs & 0x08080808u);
+                if constexpr (FP4) {
+                    const uint32_t x = raw[i][k];
+                    const v8i af = {static_cast<int>(x & 0x11111111u), static_cast<int>(x & 0x22222222u),
+                                    static_cast<int>(x & 0x44444444u), static_cast<int>((x >> 3) & 0x11111111u),
+                                    0, 0, 0, 0};
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[i][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nb], acc[i][nb], 0, 0, 0);
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const v8i b8 = {bf[nb].x, bf[nb].y, bf[nb].z, bf[nb].w, 0, 0, 0, 0};
+                        // formats 4 = FP4 (E2M1) for both operands; scales 127 = 2^0
+                        acc[i][nb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af, b8, acc[i][nb], 4, 4, 0, 127, 0, 127);
+                    }
+                } else {
+                    const uint32_t xs = j ? (raw[i][k] >> 4) : raw[i][k];
+                    v4i af;
+                    af.x = static_cast<int>(xs & 0x01010101u);
+                    af.y = static_cast<int>(xs & 0x02020202u);
+                    af.z = static_cast<int>(xs & 0x04040404u);
+                    af.w = static_cast<int>(xs & 0x08080808u);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[i][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nb], acc[i][nb], 0, 0, 0);
+                }
             }
         }
         if (st + 1 < G::STAGES) {
@@ -270,7 +311,11 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = 32 * i + 8 * (v / 4) + (v & 3);   // + 4h, in lane_off
-                const int out = s_w - (acc[i][nb][v] >> 2);
+                int out;
+                if constexpr (FP4)
+                    out = s_w - 2 * static_cast<int>(acc[i][nb][v]);   // an integer below 2^24: exact
+                else
+                    out = s_w - (acc[i][nb][v] >> 2);
                 char* row_ptr = ybase + row * row_bytes;
                 if constexpr (MASKED)
                     asm volatile("" : "+v"(rows_left));  // one compare at a time: no hoisted masks
@@ -280,7 +325,7 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
     }
 }
 
-template <int CW, int S, int MB, int NB>
+template <int CW, int S, int MB, int NB, bool FP4>
 hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
                                  const ConvShape& s, hipStream_t stream)
 {
@@ -291,27 +336,27 @@ hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int3
     const MfmaArgs p{s.H, s.W, s.Ho, s.Wo, s.pad, s.Cout, static_cast<int>(total_pix)};
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(s.Cout / (32 * NB)));
     if (total_pix >= 32 * MB)
-        bconv_mfma_bits_kernel<CW, S, MB, NB, false><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+        bconv_mfma_bits_kernel<CW, S, MB, NB, false, FP4><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
     else
-        bconv_mfma_bits_kernel<CW, S, MB, NB, true><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+        bconv_mfma_bits_kernel<CW, S, MB, NB, true, FP4><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
     return hipGetLastError();
 }
 
-template <int CW, int S>
+template <int CW, int S, bool FP4>
 hipError_t launch_mfma_bits_cw(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
                                const ConvShape& s, hipStream_t stream)
 {
     // 64 pixels x 64 channels per wavefront (three or four workgroups resident per CU).  When the
     // number of such workgroup tiles lies just above three per CU, the launch would end in a
     // nearly empty second round; wavefronts of 128 pixels halve the tile count and everything is
-    // resident at once (measured at batch 256: 14x14x256->256 26.5 us against 29.3).
+    // resident at once (measured at batch 256, int8: 14x14x256->256 26.5 us against 29.3).
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t small_tiles = ((total_pix + 255) / 256) * (s.Cout / 64);
     const int64_t cus = device_cu_count();
     const int mb = option(DABNN_OPT_MFMA_PIXEL_BLOCKS);
     if (mb == 4 || (mb == 0 && small_tiles > 3 * cus && small_tiles <= 4 * cus))
-        return launch_mfma_bits_inst<CW, S, 4, 2>(a, wq, sw, y, s, stream);
-    return launch_mfma_bits_inst<CW, S, 2, 2>(a, wq, sw, y, s, stream);
+        return launch_mfma_bits_inst<CW, S, 4, 2, FP4>(a, wq, sw, y, s, stream);
+    return launch_mfma_bits_inst<CW, S, 2, 2, FP4>(a, wq, sw, y, s, stream);
 }
 
 }  // namespace
@@ -328,34 +373,47 @@ bool bconv_mfma_bits_supports(const ConvShape& s)
            act_dwords < (int64_t{1} << 31) && total_pix < (int64_t{1} << 31) - 4096 && s.Cout <= 8192;
 }
 
-size_t mfma_weights_bytes(const ConvShape& s)
+// Operand bytes of the prepared filters: one byte (int8) or one nibble (FP4) per weight.
+static size_t mfma_operand_bytes(const ConvShape& s, int format)
 {
-    return static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw + static_cast<size_t>(s.Cout) * 4;
+    const size_t weights = static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw;
+    return format == 1 ? weights / 2 : weights;
 }
 
-hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s,
+size_t mfma_weights_bytes(const ConvShape& s, int format)
+{
+    return mfma_operand_bytes(s, format) + static_cast<size_t>(s.Cout) * 4;
+}
+
+hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s, int format,
                                        hipStream_t stream)
 {
-    if (!bconv_mfma_bits_supports(s))
+    if (!bconv_mfma_bits_supports(s) || (format != 0 && format != 1))
         return hipErrorNotSupported;
-    const int steps = 18 * s.Cw;
+    const int steps = (format == 1 ? 9 : 18) * s.Cw;
     const int64_t total = static_cast<int64_t>(s.Cout) * steps * 8;
     int8_t* q = static_cast<int8_t*>(wq);
-    int32_t* sw = reinterpret_cast<int32_t*>(q + static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw);
-    mfma_prepare_weights_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, stream>>>(
-        reinterpret_cast<const uint32_t*>(w), q, sw, s.Cout, s.Cw, steps);
+    int32_t* sw = reinterpret_cast<int32_t*>(q + mfma_operand_bytes(s, format));
+    const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
+    const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
+    if (format == 1)
+        mfma_prepare_weights_kernel<true><<<grid, block, 0, stream>>>(w32, q, sw, s.Cout, s.Cw, steps);
+    else
+        mfma_prepare_weights_kernel<false><<<grid, block, 0, stream>>>(w32, q, sw, s.Cout, s.Cw, steps);
     return hipGetLastError();
 }
 
 hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const ConvShape& s,
-                                  hipStream_t stream)
+                                  int format, hipStream_t stream)
 {
-    if (!bconv_mfma_bits_supports(s))
+    if (!bconv_mfma_bits_supports(s) || (format != 0 && format != 1))
         return hipErrorNotSupported;
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const int8_t* q = static_cast<const int8_t*>(wq);
-    const int32_t* sw = reinterpret_cast<const int32_t*>(q + static_cast<size_t>(s.Cout) * 9 * 64 * s.Cw);
-#define DABNN_CASE(CW, S) return launch_mfma_bits_cw<CW, S>(a32, q, sw, y, s, stream)
+    const int32_t* sw = reinterpret_cast<const int32_t*>(q + mfma_operand_bytes(s, format));
+#define DABNN_CASE(CW, S)                                                        \
+    return format == 1 ? launch_mfma_bits_cw<CW, S, true>(a32, q, sw, y, s, stream) \
+                       : launch_mfma_bits_cw<CW, S, false>(a32, q, sw, y, s, stream)
     switch (s.Cw * 2 + (s.stride == 2 ? 1 : 0)) {
         case 2: DABNN_CASE(1, 1);
         case 3: DABNN_CASE(1, 2);

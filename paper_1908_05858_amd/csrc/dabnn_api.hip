@@ -310,16 +310,22 @@ int dabnn_bconv2d_int8(const int8_t* a8, const int8_t* w8, int32_t* y, int N, in
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
-size_t dabnn_mfma_weights_bytes(int Cin, int Cout, int kh, int kw)
+static bool mfma_format_ok(int format)
+{
+    return format == DABNN_MFMA_INT8 || format == DABNN_MFMA_FP4;
+}
+
+size_t dabnn_mfma_weights_bytes(int Cin, int Cout, int kh, int kw, int format)
 {
     dabnn::ConvShape s;
-    if (make_shape(s, 1, kh, kw, Cin, Cout, kh, kw, 1, 0) != DABNN_OK || !dabnn::bconv_mfma_bits_supports(s))
+    if (!mfma_format_ok(format) || make_shape(s, 1, kh, kw, Cin, Cout, kh, kw, 1, 0) != DABNN_OK ||
+        !dabnn::bconv_mfma_bits_supports(s))
         return 0;
-    return dabnn::mfma_weights_bytes(s);
+    return dabnn::mfma_weights_bytes(s, format);
 }
 
 int dabnn_prepare_weights_mfma(const uint64_t* w, void* wq, int Cin, int Cout, int kh, int kw,
-                               void* stream)
+                               int format, void* stream)
 {
     if (!w || !wq)
         return DABNN_ERR_NULL;
@@ -329,14 +335,14 @@ int dabnn_prepare_weights_mfma(const uint64_t* w, void* wq, int Cin, int Cout, i
         return rc;
     if (!aligned(w, 8) || !aligned(wq, 16))
         return DABNN_ERR_ALIGN;
-    if (!dabnn::bconv_mfma_bits_supports(s))
+    if (!dabnn::bconv_mfma_bits_supports(s) || !mfma_format_ok(format))
         return DABNN_ERR_UNSUPPORTED;
-    const hipError_t e = dabnn::launch_prepare_weights_mfma(w, wq, s, static_cast<hipStream_t>(stream));
+    const hipError_t e = dabnn::launch_prepare_weights_mfma(w, wq, s, format, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 
 int dabnn_bconv2d_mfma(const uint64_t* a, const void* wq, int32_t* y, int N, int H, int W, int Cin,
-                       int Cout, int kh, int kw, int stride, int pad, void* stream)
+                       int Cout, int kh, int kw, int stride, int pad, int format, void* stream)
 {
     if (!a || !wq || !y)
         return DABNN_ERR_NULL;
@@ -346,9 +352,9 @@ int dabnn_bconv2d_mfma(const uint64_t* a, const void* wq, int32_t* y, int N, int
         return rc;
     if (!aligned(a, 16) || !aligned(wq, 16) || !aligned(y, 4))
         return DABNN_ERR_ALIGN;
-    if (!dabnn::bconv_mfma_bits_supports(s))
+    if (!dabnn::bconv_mfma_bits_supports(s) || !mfma_format_ok(format))
         return DABNN_ERR_UNSUPPORTED;
-    const hipError_t e = dabnn::launch_bconv_mfma_bits(a, wq, y, s, static_cast<hipStream_t>(stream));
+    const hipError_t e = dabnn::launch_bconv_mfma_bits(a, wq, y, s, format, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 

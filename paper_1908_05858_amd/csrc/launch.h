@@ -62,11 +62,12 @@ hipError_t launch_bconv_mfma_i8(const int8_t* a8, const int8_t* w8, int32_t* y, 
 bool bconv_mfma_supports(const ConvShape& s);
 // Matrix-core route fed from the packed activation bits; filters prepared once per model.
 bool bconv_mfma_bits_supports(const ConvShape& s);
-size_t mfma_weights_bytes(const ConvShape& s);
-hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s,
+// format 0: int8 operands, 1: FP4 (E2M1) operands.
+size_t mfma_weights_bytes(const ConvShape& s, int format);
+hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s, int format,
                                        hipStream_t stream);
 hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const ConvShape& s,
-                                  hipStream_t stream);
+                                  int format, hipStream_t stream);
 // Convolution with the BN + shortcut + sign + pack layer fused into its epilogue (no int32 tensor).
 hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, const float* scale,
                                          const float* shift, const float* r, float* x_out,

@@ -225,19 +225,24 @@ def test_mfma_route_bad_arguments_and_buffer_size(lib):
     P = ctypes.c_void_p
     a, w, y = P(0x10000), P(0x20000), P(0x30000)
     for Cin, Cout in ((64, 64), (128, 256), (256, 512), (512, 512)):
-        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, 3, 3) == Cout * 9 * Cin + 4 * Cout
+        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, 3, 3, 0) == Cout * 9 * Cin + 4 * Cout
+        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, 3, 3, 1) == Cout * 9 * Cin // 2 + 4 * Cout
     for Cin, Cout, k in ((80, 64, 3), (192, 64, 3), (64, 32, 3), (64, 64, 1), (0, 64, 3), (64, 16384, 3)):
-        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, k, k) == 0
-    assert lib.dabnn_prepare_weights_mfma(P(0), w, 64, 64, 3, 3, None) == 1
-    assert lib.dabnn_prepare_weights_mfma(a, w, 64, 0, 3, 3, None) == 2
-    assert lib.dabnn_prepare_weights_mfma(a, P(0x20008), 64, 64, 3, 3, None) == 3
-    assert lib.dabnn_prepare_weights_mfma(a, w, 80, 64, 3, 3, None) == 4
-    assert lib.dabnn_bconv2d_mfma(a, w, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 1
-    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, None) == 2
-    assert lib.dabnn_bconv2d_mfma(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, None) == 3
-    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 3, 1, None) == 4
-    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 320, 64, 3, 3, 1, 1, None) == 4
-    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 96, 3, 3, 1, 1, None) == 4
+        assert lib.dabnn_mfma_weights_bytes(Cin, Cout, k, k, 0) == 0
+    assert lib.dabnn_mfma_weights_bytes(64, 64, 3, 3, 2) == 0
+    for fmt in (0, 1):
+        assert lib.dabnn_prepare_weights_mfma(P(0), w, 64, 64, 3, 3, fmt, None) == 1
+        assert lib.dabnn_prepare_weights_mfma(a, w, 64, 0, 3, 3, fmt, None) == 2
+        assert lib.dabnn_prepare_weights_mfma(a, P(0x20008), 64, 64, 3, 3, fmt, None) == 3
+        assert lib.dabnn_prepare_weights_mfma(a, w, 80, 64, 3, 3, fmt, None) == 4
+        assert lib.dabnn_bconv2d_mfma(a, w, P(0), 1, 4, 4, 64, 64, 3, 3, 1, 1, fmt, None) == 1
+        assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, fmt, None) == 2
+        assert lib.dabnn_bconv2d_mfma(P(0x10008), w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, fmt, None) == 3
+        assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 3, 1, fmt, None) == 4
+        assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 320, 64, 3, 3, 1, 1, fmt, None) == 4
+        assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 96, 3, 3, 1, 1, fmt, None) == 4
+    assert lib.dabnn_prepare_weights_mfma(a, w, 64, 64, 3, 3, 7, None) == 4
+    assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, -1, None) == 4
 
 
 def test_layout_and_int32_pack_bad_arguments(lib):

@@ -590,25 +590,26 @@ MFMA_BITS_SHAPES = [  # N, H, W, Cin, Cout, stride, pad: every word count and st
 ]
 
 
+@pytest.mark.parametrize("fmt", [0, 1], ids=["int8", "fp4"])
 @pytest.mark.parametrize("blocks", [2, 4])
 @pytest.mark.parametrize("shape", MFMA_BITS_SHAPES, ids=lambda s: "-".join(map(str, s)))
-def test_mfma_route_from_packed_bits(dabnn, oracle, option, shape, blocks):
-    """dabnn_bconv2d_mfma (int8 matrix cores, activation operand expanded from the packed words in
-    the kernel, filters prepared by dabnn_prepare_weights_mfma) against the float oracle, every
-    output, with guard words around the output."""
+def test_mfma_route_from_packed_bits(dabnn, oracle, option, shape, blocks, fmt):
+    """dabnn_bconv2d_mfma (int8 or FP4 matrix instructions, activation operand expanded from the
+    packed words in the kernel, filters prepared by dabnn_prepare_weights_mfma) against the float
+    oracle, every output, with guard words around the output."""
     N, H, W, Cin, Cout, stride, pad = shape
-    print("mfma from bits", shape, "pixel blocks", blocks, flush=True)
+    print("mfma from bits", shape, "pixel blocks", blocks, "format", fmt, flush=True)
     option(dabnn.OPT_MFMA_PIXEL_BLOCKS, blocks)
     x = wl.activations((N, H, W, Cin), 9100 + sum(shape))
     wf = wl.weights((Cout, 3, 3, Cin), 9101 + sum(shape), 0.4)
     a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
-    n_bytes = dabnn.mfma_weights_bytes(Cin, Cout)
-    assert n_bytes == Cout * 9 * Cin + 4 * Cout
-    wq = dabnn.prepare_weights_mfma(wp, Cin)
+    n_bytes = dabnn.mfma_weights_bytes(Cin, Cout, fmt=fmt)
+    assert n_bytes == Cout * 9 * Cin // (2 if fmt else 1) + 4 * Cout
+    wq = dabnn.prepare_weights_mfma(wp, Cin, fmt=fmt)
     want = oracle.bconv2d(x, wf, stride, pad)
     buf = torch.full((want.size + 512,), -123456789, dtype=torch.int32, device="cuda")
     out = buf[256:256 + want.size].view(want.shape)
-    dabnn.bconv2d_mfma(a, wq, Cin, Cout, stride, pad, out=out)
+    dabnn.bconv2d_mfma(a, wq, Cin, Cout, stride, pad, out=out, fmt=fmt)
     got = out.cpu().numpy()
     assert torch.all(buf[:256] == -123456789) and torch.all(buf[-256:] == -123456789)
     if not np.array_equal(got, want):
@@ -617,7 +618,8 @@ def test_mfma_route_from_packed_bits(dabnn, oracle, option, shape, blocks):
                              f"got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}")
 
 
-def test_mfma_route_full_batch_layers(dabnn, oracle):
+@pytest.mark.parametrize("fmt", [0, 1], ids=["int8", "fp4"])
+def test_mfma_route_full_batch_layers(dabnn, oracle, fmt):
     """The seven layer kinds of the benchmark body at batch 256 through dabnn_bconv2d_mfma, in the
     launch configuration bench.py times, every output against the oracle."""
     seen = set()
@@ -626,11 +628,12 @@ def test_mfma_route_full_batch_layers(dabnn, oracle):
         if key in seen:
             continue
         seen.add(key)
-        print("mfma from bits, batch 256", key, flush=True)
+        print("mfma from bits, batch 256", key, "format", fmt, flush=True)
         x = wl.activations((256, L.H, L.W, L.Cin), wl.seed_for(5, 100 + li))
         wf = wl.weights((L.Cout, 3, 3, L.Cin), wl.seed_for(5, li))
         a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
-        got = dabnn.bconv2d_mfma(a, dabnn.prepare_weights_mfma(wp, L.Cin), L.Cin, L.Cout, L.stride, 1).cpu().numpy()
+        got = dabnn.bconv2d_mfma(a, dabnn.prepare_weights_mfma(wp, L.Cin, fmt=fmt), L.Cin, L.Cout, L.stride, 1,
+                                 fmt=fmt).cpu().numpy()
         want = oracle.bconv2d(x, wf, L.stride, 1)
         assert np.array_equal(got, want), key
         del a, wp, got, want
