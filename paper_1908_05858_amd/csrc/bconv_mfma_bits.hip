@@ -109,15 +109,16 @@ struct MfmaGeom {
     static constexpr int D = 2 * CW;
     static constexpr int SPD = FP4 ? 1 : 2;            // matrix instructions (steps) per dword
     static constexpr int STEPS = 9 * CW * SPD;
-    // dwords a lane consumes per LDS stage: three taps (a window row) at one word per pixel,
-    // otherwise one round
-    static constexpr int UPS = CW == 1 ? 3 : W;
+    // (tap, round) pairs of W dwords per LDS stage: a window row at one word per pixel, otherwise
+    // one pair (larger stages, i.e. fewer barriers, measured no faster)
+    static constexpr int GROUPS = CW == 1 ? 3 : 1;
+    static constexpr int UPS = GROUPS * W;             // dwords a lane consumes per stage
     static constexpr int CH = UPS * SPD;               // steps per stage
     static constexpr int STAGES = STEPS / CH;
     static constexpr int STAGE_BYTES = CH * NB * 1024;
     static constexpr int PIECES = STAGE_BYTES / 16;    // 16-byte copies per stage
     static constexpr int UNITS = (PIECES + 255) / 256; // ... per thread (the last one may be partial)
-    static_assert(STEPS % CH == 0 && PIECES % 64 == 0, "stage geometry");
+    static_assert(STEPS % CH == 0 && PIECES % 64 == 0 && (9 * R) % GROUPS == 0, "stage geometry");
 };
 
 // MASKED = false: the tensor has at least 32*MB pixels, and a wavefront whose tile would reach
@@ -171,19 +172,11 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
     // reads offset 0 and is cleared: both through an all-ones / all-zeros lane value, so that no
     // condition travels through a scalar register pair.
     auto load_a = [&](int st, uint32_t (&raw)[MB][G::UPS]) {
-        if constexpr (CW == 1) {
-            // the stage is window row ti = st: taps (st, 0..2), one dword each
+        // the stage is GROUPS consecutive (tap, round) pairs of W dwords each
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int tj = 0; tj < 3; ++tj) {
-                    const uint32_t keep = static_cast<uint32_t>(-static_cast<int>((a_valid[i] >> (st * 3 + tj)) & 1u));
-                    const uint32_t off = static_cast<uint32_t>(a_base[i] + (st * p.W + tj) * G::D) & keep;
-                    raw[i][tj] = a[off] & keep;
-                }
-        } else {
-            // the stage is round r of tap: W consecutive dwords
-            const int tap = st / G::R, r = st % G::R;
+        for (int g = 0; g < G::GROUPS; ++g) {
+            const int tr = st * G::GROUPS + g;
+            const int tap = tr / G::R, r = tr - tap * G::R;
             const int ti = tap / 3, tj = tap - 3 * ti;
             const int tap_off = (ti * p.W + tj) * G::D + 2 * G::W * r;
 #pragma unroll
@@ -192,14 +185,16 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                 const uint32_t off = static_cast<uint32_t>(a_base[i] + tap_off) & keep;
                 if constexpr (G::W == 4) {
                     const uint4 x = *reinterpret_cast<const uint4*>(a + off);
-                    raw[i][0] = x.x & keep;
-                    raw[i][1] = x.y & keep;
-                    raw[i][2] = x.z & keep;
-                    raw[i][3] = x.w & keep;
-                } else {
+                    raw[i][4 * g + 0] = x.x & keep;
+                    raw[i][4 * g + 1] = x.y & keep;
+                    raw[i][4 * g + 2] = x.z & keep;
+                    raw[i][4 * g + 3] = x.w & keep;
+                } else if constexpr (G::W == 2) {
                     const uint2 x = *reinterpret_cast<const uint2*>(a + off);
-                    raw[i][0] = x.x & keep;
-                    raw[i][1] = x.y & keep;
+                    raw[i][2 * g + 0] = x.x & keep;
+                    raw[i][2 * g + 1] = x.y & keep;
+                } else {
+                    raw[i][g] = a[off] & keep;
                 }
             }
         }
