@@ -462,6 +462,19 @@ def widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps,
             "GOPS": round(total_ops / (fused_ms * 1e-3) / 1e9, 1),
             "frac_of_valu_peak": round(total_ops / (fused_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, 4),
         }
+        # the same fused layer on the matrix-core comparison route (dabnn_bconv2d_bnsign_mfma)
+        if all(binding.mfma_weights_bytes(L.Cin, L.Cout) > 0 for L in layers):
+            for name, fmt in (("int8", binding.MFMA_INT8), ("fp4", binding.MFMA_FP4)):
+                wqs = [binding.prepare_weights_mfma(wps[li], L.Cin, fmt=fmt) for li, L in enumerate(layers)]
+
+                def fused_mfma_step():
+                    for li, L in enumerate(layers):
+                        thr, flip, out = fused_args[li]
+                        binding.bconv2d_bnsign_mfma(acts[li], wqs[li], thr, flip, L.Cin, L.Cout, L.stride, 1,
+                                                    out=out, fmt=fmt)
+                ms = wall_ms(fused_mfma_step, reps)
+                result["fused_bnsign"][f"mfma_{name}_comparison_ms_per_step"] = round(ms, 4)
+                del wqs
         del fused_args
 
         # The body with its real data dependencies (Sec. 2.3's network): each convolution reads the

@@ -281,6 +281,15 @@ int dabnn_prepare_weights_mfma(const uint64_t *w, void *wq, int Cin, int Cout, i
                                int format, void *stream);
 int dabnn_bconv2d_mfma(const uint64_t *a, const void *wq, int32_t *y, int N, int H, int W, int Cin,
                        int Cout, int kh, int kw, int stride, int pad, int format, void *stream);
+/*
+ * dabnn_bconv2d_bnsign (fused convolution + threshold + bit-pack, Sec. 2.1.1) on the matrix-core
+ * route: same arguments and results, with the prepared filters `wq` in place of the packed ones,
+ * and the shapes dabnn_bconv2d_mfma supports.  thr, flip: as written by dabnn_bn_thresholds.
+ *   out : u64 [N][Ho][Wo][Cout/64]  device, written completely.
+ */
+int dabnn_bconv2d_bnsign_mfma(const uint64_t *a, const void *wq, const int32_t *thr,
+                              const uint64_t *flip, uint64_t *out, int N, int H, int W, int Cin,
+                              int Cout, int kh, int kw, int stride, int pad, int format, void *stream);
 
 /*
  * Binary convolution with ZERO padding.  The paper builds its binary convolution on the standard

@@ -52,6 +52,8 @@ def load():
     lib.dabnn_mfma_weights_bytes.argtypes, lib.dabnn_mfma_weights_bytes.restype = [i32] * 5, ctypes.c_size_t
     lib.dabnn_prepare_weights_mfma.argtypes, lib.dabnn_prepare_weights_mfma.restype = [vp, vp] + [i32] * 5 + [vp], i32
     lib.dabnn_bconv2d_mfma.argtypes, lib.dabnn_bconv2d_mfma.restype = [vp] * 3 + [i32] * 10 + [vp], i32
+    lib.dabnn_bconv2d_bnsign_mfma.argtypes = [vp] * 5 + [i32] * 10 + [vp]
+    lib.dabnn_bconv2d_bnsign_mfma.restype = i32
     lib.dabnn_bconv2d_zeropad.argtypes, lib.dabnn_bconv2d_zeropad.restype = [vp] * 3 + [i32] * 9 + [vp], i32
     lib.dabnn_bconv2d_pick_algo.argtypes, lib.dabnn_bconv2d_pick_algo.restype = [i32] * 9, i32
     lib.dabnn_status_string.argtypes, lib.dabnn_status_string.restype = [i32], ctypes.c_char_p
@@ -70,7 +72,7 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_expand_int8", "dabnn_bconv2d_int8", "dabnn_bitpack_i32", "dabnn_nhwc_to_nc1hwc2",
            "dabnn_nc1hwc2_to_nhwc", "dabnn_bn_sign_pack", "dabnn_bconv2d_bn_residual",
            "dabnn_set_option", "dabnn_get_option", "dabnn_mfma_weights_bytes",
-           "dabnn_prepare_weights_mfma", "dabnn_bconv2d_mfma"]
+           "dabnn_prepare_weights_mfma", "dabnn_bconv2d_mfma", "dabnn_bconv2d_bnsign_mfma"]
 
 (OPT_AREG_SLOTS, OPT_AREG_TAIL, OPT_AREG_STORE, OPT_RES_CHANNELS, OPT_WREG_PIXELS, OPT_BGEMM_COLUMNS,
  OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD, OPT_MFMA_PIXEL_BLOCKS) = range(10)
@@ -348,6 +350,28 @@ def bconv2d_mfma(a, wq, Cin, Cout, stride=1, pad=1, out=None, fmt=MFMA_INT8):
     _check(load().dabnn_bconv2d_mfma(_dev(a, torch.int64, "a"), _dev(wq, torch.uint8, "wq"),
                                      _dev(out, torch.int32, "out"), N, H, W, Cin, Cout, 3, 3, stride, pad,
                                      fmt, _stream()), "dabnn_bconv2d_mfma")
+    return out
+
+
+def bconv2d_bnsign_mfma(a, wq, thr, flip, Cin, Cout, stride=1, pad=1, out=None, fmt=MFMA_INT8):
+    """bconv2d_bnsign on the matrix-core route: packed a, prepared filters wq -> int64
+    [N,Ho,Wo,Cout/64], the next layer's packed activations."""
+    N, H, W, words = a.shape
+    if words * 64 != Cin:
+        raise ValueError("packed word count does not match Cin")
+    if wq.numel() != mfma_weights_bytes(Cin, Cout, 3, 3, fmt):
+        raise ValueError("wq is not the prepared filter buffer of this layer shape and format")
+    if thr.shape != (Cout,) or flip.shape != ((Cout + 63) // 64,):
+        raise ValueError("thr / flip do not match Cout")
+    Ho, Wo = conv_out_dim(H, 3, stride, pad), conv_out_dim(W, 3, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise DabnnError(2, "dabnn_bconv2d_bnsign_mfma")
+    if out is None:
+        out = torch.empty((N, Ho, Wo, Cout // 64), dtype=torch.int64, device=a.device)
+    _check(load().dabnn_bconv2d_bnsign_mfma(_dev(a, torch.int64, "a"), _dev(wq, torch.uint8, "wq"),
+                                            _dev(thr, torch.int32, "thr"), _dev(flip, torch.int64, "flip"),
+                                            _dev(out, torch.int64, "out"), N, H, W, Cin, Cout, 3, 3, stride, pad,
+                                            fmt, _stream()), "dabnn_bconv2d_bnsign_mfma")
     return out
 
 

@@ -125,11 +125,19 @@ struct MfmaGeom {
 // past the end computes the LAST 32*MB pixels instead (some of them a second time, with the same
 // results), so that no load or store needs a bounds check.  MASKED = true: fewer pixels than one
 // tile; rows past the end repeat the last pixel and are not stored.
-template <int CW, int S, int MB, int NB, bool MASKED, bool FP4>
+//
+// BITS = true: the fused threshold epilogue of dabnn_bconv2d_bnsign.  Instead of y the kernel
+// writes the next layer's packed activations: bit c of a pixel is (y < thr[c]) XOR flip bit c.  A
+// lane holds one channel of 16 pixels, so one compare per accumulator register gives a wave-wide
+// mask whose two halves are 32 consecutive channels of two pixels: half a packed word each, which
+// lane 0 and lane 32 store.
+template <int CW, int S, int MB, int NB, bool MASKED, bool FP4, bool BITS>
 __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __restrict__ a,
                                                               const int8_t* __restrict__ wq,
                                                               const int32_t* __restrict__ sw,
                                                               int32_t* __restrict__ y,
+                                                              const int32_t* __restrict__ thr,
+                                                              const uint32_t* __restrict__ flip32,
                                                               const MfmaArgs p)
 {
     using G = MfmaGeom<CW, MB, NB, FP4>;
@@ -277,6 +285,17 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                 }
             }
         }
+        // With the fused epilogue the compiler otherwise moves the matrix instructions past all
+        // later stages (towards the compares that use their results) and keeps every operand of
+        // the whole K loop alive: an empty statement that "uses" the accumulators keeps the
+        // instructions of a stage inside the stage.
+        if constexpr (BITS) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    asm volatile("" : "+a"(acc[i][nb]));   // the stage's results exist here, in AGPRs
+        }
         if (st + 1 < G::STAGES) {
             // buffer buf^1 was last read in stage st-1, which every wavefront has left (barrier)
             store_b(buf ^ 1, stage);
@@ -293,9 +312,43 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
     // store instruction write 32 consecutive channels (128 bytes) of one pixel.
     // A row of the tile is a wave-uniform address (scalar arithmetic) plus one per-lane offset
     // that never changes: channel and the 4h rows of the upper half-wave.
+    auto output = [&](int s_w, const acc_t& c, int v) -> int {
+        if constexpr (FP4)
+            return s_w - 2 * static_cast<int>(c[v]);   // an integer below 2^24: exact
+        else
+            return s_w - (c[v] >> 2);
+    };
+    int rows_left = p.total_pix - pix0 - 4 * h;   // MASKED: this lane stores rows below that
+    if constexpr (BITS) {
+        // the packed output as 32-bit halves: [pixel][Cout/32]
+        uint32_t* out32 = reinterpret_cast<uint32_t*>(y);
+        const int halves = p.Cout >> 5;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int co = (nblk0 + nb) * 32 + m;
+            const int s_w = sw[co];
+            int t = thr[co];
+            const bool fl = (flip32[nblk0 + nb] >> m) & 1u;
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 32 * i + 8 * (v / 4) + (v & 3) + 4 * h;
+                    asm volatile("" : "+v"(t));   // one compare at a time: no 64 masks computed ahead
+                    bool below;   // y < thr
+                    if constexpr (FP4)   // S - 2 acc < t  <=>  2 acc > S - t, small integers: exact in fp32
+                        below = 2.0f * acc[i][nb][v] > static_cast<float>(s_w - t);
+                    else
+                        below = output(s_w, acc[i][nb], v) < t;
+                    const uint64_t mask = __builtin_amdgcn_ballot_w64(below != fl);
+                    const uint32_t word = h ? static_cast<uint32_t>(mask >> 32) : static_cast<uint32_t>(mask);
+                    if (m == 0 && (!MASKED || row < p.total_pix - pix0))
+                        out32[static_cast<size_t>(pix0 + row) * halves + (nblk0 + nb)] = word;
+                }
+        }
+    } else {
     char* ybase = reinterpret_cast<char*>(y) + static_cast<size_t>(pix0) * p.Cout * 4;
     const size_t row_bytes = static_cast<size_t>(p.Cout) * 4;
-    int rows_left = p.total_pix - pix0 - 4 * h;   // MASKED: this lane stores rows below that
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int co = (nblk0 + nb) * 32 + m;
@@ -306,11 +359,7 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = 32 * i + 8 * (v / 4) + (v & 3);   // + 4h, in lane_off
-                int out;
-                if constexpr (FP4)
-                    out = s_w - 2 * static_cast<int>(acc[i][nb][v]);   // an integer below 2^24: exact
-                else
-                    out = s_w - (acc[i][nb][v] >> 2);
+                const int out = output(s_w, acc[i][nb], v);
                 char* row_ptr = ybase + row * row_bytes;
                 if constexpr (MASKED)
                     asm volatile("" : "+v"(rows_left));  // one compare at a time: no hoisted masks
@@ -318,11 +367,13 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                     __builtin_nontemporal_store(out, reinterpret_cast<int*>(row_ptr + lane_off));
             }
     }
+    }
 }
 
-template <int CW, int S, int MB, int NB, bool FP4>
+template <int CW, int S, int MB, int NB, bool FP4, bool BITS>
 hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
-                                 const ConvShape& s, hipStream_t stream)
+                                 const int32_t* thr, const uint32_t* flip32, const ConvShape& s,
+                                 hipStream_t stream)
 {
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 128 * MB - 1) / (128 * MB);
@@ -331,15 +382,16 @@ hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int3
     const MfmaArgs p{s.H, s.W, s.Ho, s.Wo, s.pad, s.Cout, static_cast<int>(total_pix)};
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(s.Cout / (32 * NB)));
     if (total_pix >= 32 * MB)
-        bconv_mfma_bits_kernel<CW, S, MB, NB, false, FP4><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+        bconv_mfma_bits_kernel<CW, S, MB, NB, false, FP4, BITS><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, thr, flip32, p);
     else
-        bconv_mfma_bits_kernel<CW, S, MB, NB, true, FP4><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, p);
+        bconv_mfma_bits_kernel<CW, S, MB, NB, true, FP4, BITS><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, thr, flip32, p);
     return hipGetLastError();
 }
 
 template <int CW, int S, bool FP4>
 hipError_t launch_mfma_bits_cw(const uint32_t* a, const int8_t* wq, const int32_t* sw, int32_t* y,
-                               const ConvShape& s, hipStream_t stream)
+                               const int32_t* thr, const uint32_t* flip32, const ConvShape& s,
+                               hipStream_t stream)
 {
     // 64 pixels x 64 channels per wavefront (three or four workgroups resident per CU).  When the
     // number of such workgroup tiles lies just above three per CU, the launch would end in a
@@ -349,9 +401,15 @@ hipError_t launch_mfma_bits_cw(const uint32_t* a, const int8_t* wq, const int32_
     const int64_t small_tiles = ((total_pix + 255) / 256) * (s.Cout / 64);
     const int64_t cus = device_cu_count();
     const int mb = option(DABNN_OPT_MFMA_PIXEL_BLOCKS);
-    if (mb == 4 || (mb == 0 && small_tiles > 3 * cus && small_tiles <= 4 * cus))
-        return launch_mfma_bits_inst<CW, S, 4, 2, FP4>(a, wq, sw, y, s, stream);
-    return launch_mfma_bits_inst<CW, S, 2, 2, FP4>(a, wq, sw, y, s, stream);
+    const bool big = mb == 4 || (mb == 0 && small_tiles > 3 * cus && small_tiles <= 4 * cus);
+    if (thr != nullptr) {   // fused threshold epilogue: packed words instead of y
+        if (big)
+            return launch_mfma_bits_inst<CW, S, 4, 2, FP4, true>(a, wq, sw, y, thr, flip32, s, stream);
+        return launch_mfma_bits_inst<CW, S, 2, 2, FP4, true>(a, wq, sw, y, thr, flip32, s, stream);
+    }
+    if (big)
+        return launch_mfma_bits_inst<CW, S, 4, 2, FP4, false>(a, wq, sw, y, thr, flip32, s, stream);
+    return launch_mfma_bits_inst<CW, S, 2, 2, FP4, false>(a, wq, sw, y, thr, flip32, s, stream);
 }
 
 }  // namespace
@@ -398,17 +456,19 @@ hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvSh
     return hipGetLastError();
 }
 
-hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const ConvShape& s,
-                                  int format, hipStream_t stream)
+hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const int32_t* thr,
+                                  const uint64_t* flip, const ConvShape& s, int format,
+                                  hipStream_t stream)
 {
     if (!bconv_mfma_bits_supports(s) || (format != 0 && format != 1))
         return hipErrorNotSupported;
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const int8_t* q = static_cast<const int8_t*>(wq);
     const int32_t* sw = reinterpret_cast<const int32_t*>(q + mfma_operand_bytes(s, format));
+    const uint32_t* f32 = reinterpret_cast<const uint32_t*>(flip);
 #define DABNN_CASE(CW, S)                                                        \
-    return format == 1 ? launch_mfma_bits_cw<CW, S, true>(a32, q, sw, y, s, stream) \
-                       : launch_mfma_bits_cw<CW, S, false>(a32, q, sw, y, s, stream)
+    return format == 1 ? launch_mfma_bits_cw<CW, S, true>(a32, q, sw, y, thr, f32, s, stream) \
+                       : launch_mfma_bits_cw<CW, S, false>(a32, q, sw, y, thr, f32, s, stream)
     switch (s.Cw * 2 + (s.stride == 2 ? 1 : 0)) {
         case 2: DABNN_CASE(1, 1);
         case 3: DABNN_CASE(1, 2);

@@ -354,7 +354,27 @@ int dabnn_bconv2d_mfma(const uint64_t* a, const void* wq, int32_t* y, int N, int
         return DABNN_ERR_ALIGN;
     if (!dabnn::bconv_mfma_bits_supports(s) || !mfma_format_ok(format))
         return DABNN_ERR_UNSUPPORTED;
-    const hipError_t e = dabnn::launch_bconv_mfma_bits(a, wq, y, s, format, static_cast<hipStream_t>(stream));
+    const hipError_t e = dabnn::launch_bconv_mfma_bits(a, wq, y, nullptr, nullptr, s, format,
+                                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
+}
+
+int dabnn_bconv2d_bnsign_mfma(const uint64_t* a, const void* wq, const int32_t* thr,
+                              const uint64_t* flip, uint64_t* out, int N, int H, int W, int Cin,
+                              int Cout, int kh, int kw, int stride, int pad, int format, void* stream)
+{
+    if (!a || !wq || !thr || !flip || !out)
+        return DABNN_ERR_NULL;
+    dabnn::ConvShape s;
+    const int rc = make_shape(s, N, H, W, Cin, Cout, kh, kw, stride, pad);
+    if (rc != DABNN_OK)
+        return rc;
+    if (!aligned(a, 16) || !aligned(wq, 16) || !aligned(thr, 4) || !aligned(flip, 8) || !aligned(out, 8))
+        return DABNN_ERR_ALIGN;
+    if (!dabnn::bconv_mfma_bits_supports(s) || !mfma_format_ok(format))
+        return DABNN_ERR_UNSUPPORTED;
+    const hipError_t e = dabnn::launch_bconv_mfma_bits(a, wq, reinterpret_cast<int32_t*>(out), thr, flip, s,
+                                                       format, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;
 }
 

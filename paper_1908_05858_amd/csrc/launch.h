@@ -66,8 +66,11 @@ bool bconv_mfma_bits_supports(const ConvShape& s);
 size_t mfma_weights_bytes(const ConvShape& s, int format);
 hipError_t launch_prepare_weights_mfma(const uint64_t* w, void* wq, const ConvShape& s, int format,
                                        hipStream_t stream);
-hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const ConvShape& s,
-                                  int format, hipStream_t stream);
+// thr == nullptr: y is the int32 output; otherwise y is the packed output of the fused threshold
+// epilogue (u64 [N][Ho][Wo][Cout/64]), bit c = (conv < thr[c]) XOR bit c of flip.
+hipError_t launch_bconv_mfma_bits(const uint64_t* a, const void* wq, int32_t* y, const int32_t* thr,
+                                  const uint64_t* flip, const ConvShape& s, int format,
+                                  hipStream_t stream);
 // Convolution with the BN + shortcut + sign + pack layer fused into its epilogue (no int32 tensor).
 hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, const float* scale,
                                          const float* shift, const float* r, float* x_out,

@@ -241,6 +241,10 @@ def test_mfma_route_bad_arguments_and_buffer_size(lib):
         assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 3, 1, fmt, None) == 4
         assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 320, 64, 3, 3, 1, 1, fmt, None) == 4
         assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 96, 3, 3, 1, 1, fmt, None) == 4
+        assert lib.dabnn_bconv2d_bnsign_mfma(a, w, P(0), y, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, fmt, None) == 1
+        assert lib.dabnn_bconv2d_bnsign_mfma(a, w, y, y, y, 1, 4, 4, 64, 64, 3, 3, 1, 3, fmt, None) == 2
+        assert lib.dabnn_bconv2d_bnsign_mfma(a, w, P(0x30002), y, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, fmt, None) == 3
+        assert lib.dabnn_bconv2d_bnsign_mfma(a, w, y, y, y, 1, 4, 4, 64, 96, 3, 3, 1, 1, fmt, None) == 4
     assert lib.dabnn_prepare_weights_mfma(a, w, 64, 64, 3, 3, 7, None) == 4
     assert lib.dabnn_bconv2d_mfma(a, w, y, 1, 4, 4, 64, 64, 3, 3, 1, 1, -1, None) == 4
 

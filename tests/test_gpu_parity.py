@@ -639,6 +639,30 @@ def test_mfma_route_full_batch_layers(dabnn, oracle, fmt):
         del a, wp, got, want
 
 
+@pytest.mark.parametrize("fmt", [0, 1], ids=["int8", "fp4"])
+@pytest.mark.parametrize("blocks", [2, 4])
+@pytest.mark.parametrize("shape", MFMA_BITS_SHAPES[::2] + [(256, 14, 14, 256, 256, 1, 1)],
+                         ids=lambda s: "-".join(map(str, s)))
+def test_mfma_route_fused_threshold(dabnn, oracle, option, shape, blocks, fmt):
+    """dabnn_bconv2d_bnsign_mfma: the packed next-layer activations against the oracle's
+    sign(BN(conv)) in fp64, every word, with guard words; thresholds from dabnn_bn_thresholds."""
+    N, H, W, Cin, Cout, stride, pad = shape
+    print("mfma fused threshold", shape, "pixel blocks", blocks, "format", fmt, flush=True)
+    option(dabnn.OPT_MFMA_PIXEL_BLOCKS, blocks)
+    x = wl.activations((N, H, W, Cin), 9300 + sum(shape))
+    wf = wl.weights((Cout, 3, 3, Cin), 9301 + sum(shape))
+    gamma, beta, mean, var = _bn_params(Cout, 9302 + sum(shape))
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * Cin)
+    a, wp = dabnn.bitpack(gpu(x)), dabnn.pack_weights(gpu(wf))
+    wq = dabnn.prepare_weights_mfma(wp, Cin, fmt=fmt)
+    want = oracle.bconv2d_bnsign(x, wf, gamma, beta, mean, var, 1e-5, stride, pad)
+    buf = torch.full((want.size + 64,), 0x5a5a5a5a5a5a5a5a, dtype=torch.int64, device="cuda")
+    out = buf[32:32 + want.size].view(want.shape)
+    dabnn.bconv2d_bnsign_mfma(a, wq, thr, flip, Cin, Cout, stride, pad, out=out, fmt=fmt)
+    assert torch.all(buf[:32] == 0x5a5a5a5a5a5a5a5a) and torch.all(buf[-32:] == 0x5a5a5a5a5a5a5a5a)
+    assert np.array_equal(words(out), want)
+
+
 def test_mfma_route_refuses_what_it_does_not_cover(dabnn):
     assert dabnn.mfma_weights_bytes(80, 64) == 0 and dabnn.mfma_weights_bytes(64, 48) == 0
     assert dabnn.mfma_weights_bytes(192, 64) == 0 and dabnn.mfma_weights_bytes(64, 64, 5, 5) == 0
