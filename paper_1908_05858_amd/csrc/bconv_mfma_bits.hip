@@ -11,15 +11,15 @@
 //   step j in {0, 1} of that word uses xs = x >> 4j, and operand register v in 0..3 is
 //   xs & (0x01010101 << v): byte b holds bit 4j + v + 8b of x, as the value 2^v.
 // One AND per operand register.  The weights are prepared once per model in exactly that order
-// (dabnn_prepare_weights_mfma): byte (h, v, b) of a step is s * 2^(3 - v), so every product is
-// +-8 a and the accumulator holds 8 * sum a s; y = S - acc / 4.
+// (dabnn_prepare_weights_mfma): byte (h, v, b) of a step is -s * 2^(3 - v), so every product is
+// -+8 a; the accumulators start at 4 S and end at 4 S - 8 sum a s = 4 y: one shift per output.
 //
 // FP4 mode (v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in the 4-bit E2M1 format, scales
 // 1.0): twice the products per instruction.  One 32-bit word x per lane is one whole operand: the
 // registers are x & 0x11111111 (bit 4k as the value 0.5 in nibble k), x & 0x22222222 (bit 4k+1 as
 // 1.0), x & 0x44444444 (bit 4k+2 as 2.0) and (x >> 3) & 0x11111111 (bit 4k+3 as 0.5); the prepared
-// weights are s * 2, s * 1, s * 0.5, s * 2 in the same places, so every product is +-a exactly and
-// the fp32 accumulator holds the integer sum a s; y = S - 2 acc.
+// weights are -s * 4, -s * 2, -s * 1, -s * 4 in the same places, so every product is -+2 a exactly
+// and the fp32 accumulators, which start at S, end at the integer S - 2 sum a s = y.
 //
 //   mfma_prepare_weights_kernel : packed filters -> [Cout/32][steps][64 lanes][16 B], S[Cout]
 //   bconv_mfma_bits_kernel      : a wavefront owns 32*MB pixels x 32*NB channels (MB x NB
@@ -32,8 +32,7 @@
 #include <cstdint>
 #include <type_traits>
 
-#include "kernel_util.h"
-#include "launch.h"
+#include "bconv_areg_common.h"   // fast_div, division_constants
 
 namespace dabnn {
 namespace {
@@ -71,18 +70,20 @@ __global__ __launch_bounds__(256) void mfma_prepare_weights_kernel(
         const uint32_t x = wp[(static_cast<int64_t>(n) * 9 + tap) * D + 2 * W * r + W * h + q];
         uint32_t out = 0;
         if (FP4) {
-            // E2M1: 0.5 = 0001, 1.0 = 0010, 2.0 = 0100, sign = 1000
-            const uint32_t magnitude = v == 1 ? 0x2u : (v == 2 ? 0x1u : 0x4u);
+            // -2 s / (the activation bit's value 0.5, 1, 2, 0.5) in E2M1: 1.0 = 0010, 2.0 = 0100,
+            // 4.0 = 0110, sign = 1000
+            const uint32_t magnitude = v == 1 ? 0x4u : (v == 2 ? 0x2u : 0x6u);
             for (int k = 0; k < 8; ++k) {
                 const uint32_t bit = (x >> (4 * k + v)) & 1u;
-                out |= (magnitude | (bit ? 0x8u : 0u)) << (4 * k);
+                out |= (magnitude | (bit ? 0u : 0x8u)) << (4 * k);
             }
         } else {
-        for (int b = 0; b < 4; ++b) {
-            const uint32_t bit = (x >> (4 * j + v + 8 * b)) & 1u;
-            const int val = (bit ? -1 : 1) * (8 >> v);
-            out |= (static_cast<uint32_t>(val) & 0xffu) << (8 * b);
-        }
+            // -8 s / (the activation bit's value 2^v)
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t bit = (x >> (4 * j + v + 8 * b)) & 1u;
+                const int val = (bit ? 1 : -1) * (8 >> v);
+                out |= (static_cast<uint32_t>(val) & 0xffu) << (8 * b);
+            }
         }
         // [n/32][t][lane = 32h + n%32][16 bytes = 4 registers]
         const int64_t o = ((static_cast<int64_t>(n >> 5) * steps + t) * 64 + 32 * h + (n & 31)) * 16 + 4 * v;
@@ -100,6 +101,8 @@ __global__ __launch_bounds__(256) void mfma_prepare_weights_kernel(
 
 struct MfmaArgs {
     int H, W, Ho, Wo, pad, Cout, total_pix;
+    uint32_t hw, hw_mul, hw_shift;   // Ho*Wo and its multiply-shift division constants
+    uint32_t wo_mul, wo_shift;       // those of Wo
 };
 
 template <int CW, int MB, int NB, bool FP4>
@@ -159,21 +162,20 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
         const int pc = min(pix0 + 32 * i + m, p.total_pix - 1);  // rows past the end repeat
-        const int n = pc / (p.Ho * p.Wo);
-        const int rem = pc - n * (p.Ho * p.Wo);
-        const int ho = rem / p.Wo;
+        const int n = static_cast<int>(fast_div(static_cast<uint32_t>(pc), p.hw_mul, p.hw_shift));
+        const int rem = pc - n * static_cast<int>(p.hw);
+        const int ho = static_cast<int>(fast_div(static_cast<uint32_t>(rem), p.wo_mul, p.wo_shift));
         const int hi0 = ho * S - p.pad;
         const int wi0 = (rem - ho * p.Wo) * S - p.pad;
         a_base[i] = ((n * p.H + hi0) * p.W + wi0) * G::D + G::W * h;
-        uint32_t mask = 0;
+        // bit 3 ti + tj: row hi0 + ti and column wi0 + tj inside the image
+        uint32_t rows = 0, cols = 0;
 #pragma unroll
-        for (int ti = 0; ti < 3; ++ti)
-#pragma unroll
-            for (int tj = 0; tj < 3; ++tj)
-                if (static_cast<unsigned>(hi0 + ti) < static_cast<unsigned>(p.H) &&
-                    static_cast<unsigned>(wi0 + tj) < static_cast<unsigned>(p.W))
-                    mask |= 1u << (ti * 3 + tj);
-        a_valid[i] = mask;
+        for (int t = 0; t < 3; ++t) {
+            rows |= (static_cast<unsigned>(hi0 + t) < static_cast<unsigned>(p.H) ? 1u : 0u) << (3 * t);
+            cols |= (static_cast<unsigned>(wi0 + t) < static_cast<unsigned>(p.W) ? 1u : 0u) << t;
+        }
+        a_valid[i] = (rows * 7u) & (cols * 0x49u);
     }
 
     // The activation dwords of stage st for this lane: raw[i][k], k < UPS.  A tap outside the image
@@ -228,15 +230,23 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                 *reinterpret_cast<v4i*>(&lds_b[buf][(tid + 256 * k) * 16]) = stage[k];
     };
 
+    // every accumulator register of a lane belongs to one output channel: they start at that
+    // channel's constant (4 S for int8, S for FP4) and the matrix instructions subtract from it
     using acc_t = std::conditional_t<FP4, v16f, v16i>;
     acc_t acc[MB][NB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+    for (int nb = 0; nb < NB; ++nb) {
+        const int s_w = sw[(nblk0 + nb) * 32 + m];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                acc[i][nb][v] = 0;
+            for (int v = 0; v < 16; ++v) {
+                if constexpr (FP4)
+                    acc[i][nb][v] = static_cast<float>(s_w);
+                else
+                    acc[i][nb][v] = 4 * s_w;
+            }
+    }
 
     uint32_t raw[MB][G::UPS], raw_next[MB][G::UPS];
     v4i stage[G::UNITS];
@@ -312,11 +322,11 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
     // store instruction write 32 consecutive channels (128 bytes) of one pixel.
     // A row of the tile is a wave-uniform address (scalar arithmetic) plus one per-lane offset
     // that never changes: channel and the 4h rows of the upper half-wave.
-    auto output = [&](int s_w, const acc_t& c, int v) -> int {
+    auto output = [&](const acc_t& c, int v) -> int {
         if constexpr (FP4)
-            return s_w - 2 * static_cast<int>(c[v]);   // an integer below 2^24: exact
+            return static_cast<int>(c[v]);   // an integer below 2^24: exact
         else
-            return s_w - (c[v] >> 2);
+            return c[v] >> 2;                // a multiple of 4
     };
     int rows_left = p.total_pix - pix0 - 4 * h;   // MASKED: this lane stores rows below that
     if constexpr (BITS) {
@@ -326,7 +336,6 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int co = (nblk0 + nb) * 32 + m;
-            const int s_w = sw[co];
             int t = thr[co];
             const bool fl = (flip32[nblk0 + nb] >> m) & 1u;
 #pragma unroll
@@ -335,12 +344,7 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                 for (int v = 0; v < 16; ++v) {
                     const int row = 32 * i + 8 * (v / 4) + (v & 3) + 4 * h;
                     asm volatile("" : "+v"(t));   // one compare at a time: no 64 masks computed ahead
-                    bool below;   // y < thr
-                    if constexpr (FP4)   // S - 2 acc < t  <=>  2 acc > S - t, small integers: exact in fp32
-                        below = 2.0f * acc[i][nb][v] > static_cast<float>(s_w - t);
-                    else
-                        below = output(s_w, acc[i][nb], v) < t;
-                    const uint64_t mask = __builtin_amdgcn_ballot_w64(below != fl);
+                    const uint64_t mask = __builtin_amdgcn_ballot_w64((output(acc[i][nb], v) < t) != fl);
                     const uint32_t word = h ? static_cast<uint32_t>(mask >> 32) : static_cast<uint32_t>(mask);
                     if (m == 0 && (!MASKED || row < p.total_pix - pix0))
                         out32[static_cast<size_t>(pix0 + row) * halves + (nblk0 + nb)] = word;
@@ -352,14 +356,13 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int co = (nblk0 + nb) * 32 + m;
-        const int s_w = sw[co];
         const uint32_t lane_off = (static_cast<uint32_t>(4 * h) * p.Cout + co) * 4u;
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = 32 * i + 8 * (v / 4) + (v & 3);   // + 4h, in lane_off
-                const int out = output(s_w, acc[i][nb], v);
+                const int out = output(acc[i][nb], v);
                 char* row_ptr = ybase + row * row_bytes;
                 if constexpr (MASKED)
                     asm volatile("" : "+v"(rows_left));  // one compare at a time: no hoisted masks
@@ -379,7 +382,10 @@ hipError_t launch_mfma_bits_inst(const uint32_t* a, const int8_t* wq, const int3
     const int64_t tiles = (total_pix + 128 * MB - 1) / (128 * MB);
     if (tiles > 0x7fffffff)
         return hipErrorNotSupported;
-    const MfmaArgs p{s.H, s.W, s.Ho, s.Wo, s.pad, s.Cout, static_cast<int>(total_pix)};
+    MfmaArgs p{s.H, s.W, s.Ho, s.Wo, s.pad, s.Cout, static_cast<int>(total_pix), 0, 0, 0, 0, 0};
+    p.hw = static_cast<uint32_t>(s.Ho) * static_cast<uint32_t>(s.Wo);
+    division_constants(p.hw, p.hw_mul, p.hw_shift);
+    division_constants(static_cast<uint32_t>(s.Wo), p.wo_mul, p.wo_shift);
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(s.Cout / (32 * NB)));
     if (total_pix >= 32 * MB)
         bconv_mfma_bits_kernel<CW, S, MB, NB, false, FP4, BITS><<<grid, dim3(256), 0, stream>>>(a, wq, sw, y, thr, flip32, p);
