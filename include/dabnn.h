@@ -55,9 +55,11 @@ typedef enum {
     DABNN_ALGO_REFERENCE = 1, /* one thread per output, any shape; the GPU-side safety net */
     DABNN_ALGO_WREG = 2,      /* weights resident in VGPRs, activations broadcast through SGPRs;
                                  3x3 kernels with ceil(Cin/64) in {1,2,4,8}, stride 1 or 2 */
-    DABNN_ALGO_AREG = 3,      /* each lane keeps one output pixel's 3x3 window in VGPRs, weights are
-                                 broadcast through SGPRs; 3x3 kernels with ceil(Cin/64) in
-                                 {1,2,4,8}, stride 1 or 2, Cout % 4 == 0 (8 for Cin <= 64), y 16-byte aligned */
+    DABNN_ALGO_AREG = 3,      /* each lane keeps one output pixel's 3x3 window (or, from 8 words per pixel
+                                 on, a quarter of it) in VGPRs, weights are broadcast through SGPRs; 3x3
+                                 kernels, stride 1 or 2, any Cin; Cout % 4 == 0 (% 8 for an odd number of
+                                 words per pixel, % 16 above 8 words), y 16-byte aligned, packed
+                                 activations below 4 GiB */
     DABNN_ALGO_BGEMM = 4      /* 1x1, stride 1, pad 0 only: the convolution IS the BGEMM of Eq. 1;
                                  Cout % 16 == 0, y 16-byte aligned, row lengths dabnn_bgemm's
                                  fast kernel supports */
