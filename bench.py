@@ -303,9 +303,18 @@ def main():
             "frac_of_hbm_peak": round(moved / med / 1e3 / HBM_PEAK_GBPS, 4)}
         del xb, ob
 
+    # The sections below are reported beside the headline; a failure in one of them is recorded in
+    # the line instead of losing the headline that is already measured.
     if not args.headline_only:
-        result["configs"] = other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle)
-        widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps, ys, total_ops, wall_ms, launch_us)
+        try:
+            result["configs"] = other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle)
+        except Exception as e:  # noqa: BLE001
+            result["configs_error"] = repr(e)
+        try:
+            widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps, ys, total_ops, wall_ms,
+                         launch_us)
+        except Exception as e:  # noqa: BLE001
+            result["widened_rows_error"] = repr(e)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     if want_oracle:
