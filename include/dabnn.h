@@ -85,7 +85,8 @@ typedef enum {
     DABNN_OPT_RES_CHANNELS = 3,    /* 16: 16-channel groups in dabnn_bconv2d_bn_residual's fused kernel */
     DABNN_OPT_WREG_PIXELS = 4,     /* 7 or 8: output pixels per task of DABNN_ALGO_WREG */
     DABNN_OPT_BGEMM_COLUMNS = 5,   /* 16: 16-column groups in dabnn_bgemm's fast kernel */
-    DABNN_OPT_BITPACK_ROWWISE = 6, /* 1: the row-wise kernel for channel counts that are no multiple of 64 */
+    DABNN_OPT_BITPACK_ROWWISE = 6, /* channel counts that are no multiple of 64: 1 the row-wise kernel, 2 the
+                                      flat-stream kernel with 64-bit indices (by default only from 2^31 elements) */
     DABNN_OPT_AREG_SPLIT = 7,      /* DABNN_ALGO_AREG kernels in which the four wavefronts of a workgroup share a
                                       channel group (always used above 8 words per pixel, by default at 8 when
                                       Cout % 16 == 0 and the launch has 3 or more groups per CU): 1 not below 9

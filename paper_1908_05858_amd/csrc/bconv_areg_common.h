@@ -99,32 +99,6 @@ __device__ __forceinline__ void shift_in(uint32_t& bits, int d, int kt)
     bits = __builtin_amdgcn_alignbit(bits, static_cast<uint32_t>(t), 31);
 }
 
-// floor(n / d) for any 32-bit n, with mul = floor(2^32 * (2^L - d) / d) + 1 and shift = L - 1,
-// L = ceil(log2 d) (d = 1: mul = 0 would need a 33-bit step, so the host passes shift = 32,
-// which selects the identity).
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t shift)
-{
-    if (shift == 32)
-        return n;
-    const uint32_t t = __umulhi(mul, n);
-    return (t + ((n - t) >> 1)) >> shift;
-}
-
-// Constants of fast_div for the divisor d >= 1.
-inline void division_constants(uint32_t d, uint32_t& mul, uint32_t& shift)
-{
-    if (d == 1) {
-        mul = 0;
-        shift = 32;
-        return;
-    }
-    uint32_t L = 0;
-    while ((uint64_t{1} << L) < d)
-        ++L;  // L = ceil(log2 d) >= 1
-    mul = static_cast<uint32_t>(((uint64_t{1} << 32) * ((uint64_t{1} << L) - d)) / d + 1);
-    shift = L - 1;
-}
-
 constexpr int kDC = 6;   // dwords per channel in one unit of the scalar-load pipeline
 
 }  // namespace

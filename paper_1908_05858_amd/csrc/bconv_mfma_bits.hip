@@ -32,7 +32,8 @@
 #include <cstdint>
 #include <type_traits>
 
-#include "bconv_areg_common.h"   // fast_div, division_constants
+#include "kernel_util.h"   // fast_div, division_constants
+#include "launch.h"
 
 namespace dabnn {
 namespace {

@@ -88,77 +88,126 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_kernel(
 // masked lanes, the tensor is read as ONE flat stream of floats in aligned 64-element chunks
 // (every load a full coalesced 256-byte run); each chunk's 64 sign bits form a ballot, and an
 // output word is a bit-field of that flat bit stream: word (p, j) starts at flat bit p*C + 64*j
-// and is min(64, C - 64*j) bits long.  A wavefront produces 32 consecutive output words: it loads
-// the (at most 33) chunks they touch, parks ballot k in lane k, and lane w then assembles word w
-// from two neighbouring ballots with a funnel shift and a length mask.
-constexpr int kTailWords = 32;
+// and is min(64, C - 64*j) bits long.
+//
+// A wavefront owns 32 consecutive chunks (8 KB of input, whatever C is) and produces the words
+// that START in them: it loads those chunks and the next one (a word may end there), parks ballot
+// k in lane k (v_writelane), and lane l then assembles its word from two neighbouring ballots
+// with a funnel shift and a length mask; 64 words per pass, as many passes as the chunks hold
+// word starts (one for C >= 32).  The first word that starts at or after flat bit B is
+// (B / C) * Cw + ceil((B % C) / 64).
+//
+// Every output word uses exactly the flat bits [start, start + len), all of them inside the
+// tensor, so whatever the clamped loads at the tensor's end bring in is shifted or masked away.
+//
+// The kernel is built to issue few instructions, because at 33 loads per 8 KB the instruction
+// count, not HBM, bounds it otherwise: everything per wavefront is scalar, the loads of a
+// wavefront inside the tensor share one scalar base address and differ in their immediate
+// offsets, and divisions are a multiply and a shift.  WIDE = false covers tensors below 2^31
+// elements in 32-bit arithmetic; WIDE = true does the per-wavefront part in 64 bits (real
+// divisions) for anything larger.
+constexpr int kTailChunks = 32;
 
-template <int MODE>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
-    const uint32_t* __restrict__ x, uint2* __restrict__ out, int64_t n_words, int64_t n_floats,
-    int C, int Cw)
+// Lane K of `blo` / `bhi` takes the scalars `lo` / `hi` (v_writelane_b32).  The scalars come from
+// a vector compare just before; gfx950 wants wait states between a vector instruction's write of
+// a scalar register and a vector instruction's read of it, which the compiler cannot see inside
+// an asm statement, so the statement brings its own (4).
+template <int K>
+__device__ __forceinline__ void park_in_lane(int& blo, int& bhi, uint32_t lo, uint32_t hi)
 {
+    asm("s_nop 3\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+        : "+v"(blo), "+v"(bhi)
+        : "s"(lo), "s"(hi), "n"(K));
+}
+
+struct TailArgs {
+    int64_t n_words, n_floats;
+    int C, Cw;
+    uint32_t c_mul, c_shift;    // fast_div constants of C
+    uint32_t cw_mul, cw_shift;  // ... of Cw
+};
+
+template <int MODE, bool WIDE>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
+    const uint32_t* __restrict__ x, uint2* __restrict__ out, const TailArgs a)
+{
+    using index_t = std::conditional_t<WIDE, int64_t, uint32_t>;
+    const index_t n_words = static_cast<index_t>(a.n_words);
+    const index_t n_floats = static_cast<index_t>(a.n_floats);
+    const int C = a.C, Cw = a.Cw;
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t w0 =
-        (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block) * kTailWords;
-    if (w0 >= n_words)
+    const index_t c0 =
+        (static_cast<index_t>(blockIdx.x) * kWavesPerBlock + wave_in_block) * kTailChunks;
+    const index_t B0 = c0 * 64;   // first flat bit (= element) of this wavefront
+    if (B0 >= n_floats)
         return;
-    // flat bit range [s0, e1) of this wavefront's words, and the chunks that cover it
-    const int64_t p0 = w0 / Cw;
-    const int64_t s0 = p0 * C + 64 * (w0 - p0 * Cw);
-    const int64_t w1 = min(w0 + kTailWords, n_words) - 1;
-    const int64_t p1 = w1 / Cw;
-    const int64_t j1 = w1 - p1 * Cw;
-    const int64_t e1 = p1 * C + min<int64_t>(64 * j1 + 64, C);
-    const int64_t c_first = s0 >> 6;
-    const int n_chunks = static_cast<int>(((e1 - 1) >> 6) - c_first) + 1;  // <= kTailWords + 1
 
-    uint32_t v[kTailWords + 1];
-#pragma unroll
-    for (int k = 0; k <= kTailWords; ++k) {
-        // always a valid address (no branch around the load, so all 33 stay in flight); chunks
-        // and elements past the end are zeroed afterwards
-        const int64_t idx = (c_first + k) * 64 + lane;
-        v[k] = __builtin_nontemporal_load(x + min(idx, n_floats - 1));
+    // pixel of flat bit B, and the first word that starts at or after B
+    auto pixel_of = [&](index_t B) -> index_t {
+        if constexpr (WIDE)
+            return B / C;
+        else
+            return fast_div(B, a.c_mul, a.c_shift);
+    };
+    const index_t pA = pixel_of(B0);
+    const int jA = (static_cast<int>(B0 - pA * C) + 63) >> 6;   // <= Cw: then it is (pA + 1, 0)
+    const index_t wA = pA * Cw + jA;
+    index_t wB = n_words;
+    if (B0 + 64 * kTailChunks < n_floats) {
+        const index_t pB = pixel_of(B0 + 64 * kTailChunks);
+        wB = pB * Cw + ((static_cast<int>(B0 + 64 * kTailChunks - pB * C) + 63) >> 6);
     }
+    const int count = static_cast<int>(wB - wA);   // words that start in these chunks
+
+    const index_t avail = n_floats - B0;   // floats from the first chunk to the tensor's end: > 0
+    const uint32_t* src = x + static_cast<size_t>(B0);   // wave-uniform
+    uint32_t v[kTailChunks + 1];
+    if (avail >= static_cast<index_t>(64 * (kTailChunks + 1))) {
 #pragma unroll
-    for (int k = 0; k <= kTailWords; ++k) {
-        const int64_t idx = (c_first + k) * 64 + lane;
-        v[k] = (k < n_chunks && idx < n_floats) ? v[k] : 0u;
+        for (int k = 0; k <= kTailChunks; ++k)
+            v[k] = __builtin_nontemporal_load(src + k * 64 + lane);
+        // (an empty statement at the end of this branch only: without it the compiler merges the
+        // two branches into one sequence of loads from 33 separately computed addresses)
+        asm volatile("");
+    } else {
+        // the tensor ends inside these chunks: loads past the end re-read its last element
+        const uint32_t last = static_cast<uint32_t>(avail) - 1;
+#pragma unroll
+        for (int k = 0; k <= kTailChunks; ++k)
+            v[k] = src[min(static_cast<uint32_t>(k * 64 + lane), last)];
     }
-    uint32_t blo = 0, bhi = 0;  // lane k: the sign bits of chunk c_first + k
-    static_for<0, kTailWords + 1>([&](auto kc) {
+    int blo = 0, bhi = 0;  // lane k: the sign bits of chunk c0 + k
+    static_for<0, kTailChunks + 1>([&](auto kc) {
         constexpr int k = decltype(kc)::value;
         const uint64_t word = __builtin_amdgcn_ballot_w64(negative_bit<MODE>(v[k]));
-        if (lane == k) {
-            blo = static_cast<uint32_t>(word);
-            bhi = static_cast<uint32_t>(word >> 32);
-        }
+        park_in_lane<k>(blo, bhi, static_cast<uint32_t>(word), static_cast<uint32_t>(word >> 32));
     });
 
-    // lane w < 32 assembles output word w0 + w; all of it in 32-bit arithmetic relative to the
-    // wavefront's first pixel (64-bit divisions happen once per wavefront, above, on scalars)
-    const int j0 = static_cast<int>(w0 - p0 * Cw);
-    const int base = static_cast<int>(p0 * C - c_first * 64);  // flat bit of pixel p0, chunk-relative
-    const int last = static_cast<int>(w1 - w0);
-    const int q = j0 + min(lane & (kTailWords - 1), last);
-    const int dp = q / Cw;
-    const int j = q - dp * Cw;
-    const int rel = base + dp * C + 64 * j;  // 0 <= rel < 64 * (kTailWords + 1)
-    const int src = rel >> 6, off = rel & 63;
-    const int len = min(64, C - 64 * j);
-    const uint64_t b0 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(static_cast<int>(bhi), src))) << 32) |
-                        static_cast<uint32_t>(__shfl(static_cast<int>(blo), src));
-    const uint64_t b1 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(static_cast<int>(bhi), src + 1))) << 32) |
-                        static_cast<uint32_t>(__shfl(static_cast<int>(blo), src + 1));
-    uint64_t word = b0 >> off;
-    if (off != 0)
-        word |= b1 << (64 - off);
-    if (len < 64)
-        word &= (uint64_t{1} << len) - 1;  // bits past the pixel's last channel are 0
-    if (lane < kTailWords && w0 + lane < n_words)
-        out[w0 + lane] = make_uint2(static_cast<uint32_t>(word), static_cast<uint32_t>(word >> 32));
+    // lane l assembles word wA + l (+ 64 per further pass), in 32-bit arithmetic relative to the
+    // first chunk: flat bit of pixel pA minus B0 (negative when the pixel starts before the chunk)
+    const int base = -static_cast<int>(B0 - pA * C);
+    // (every lane takes part in the lane exchange of every pass; only the store is conditional)
+    for (int first = 0; first < count; first += 64) {
+        const int l = first + lane;
+        const int q = jA + min(l, count - 1);   // word index counted from pixel pA's first word
+        const int dp = static_cast<int>(fast_div(static_cast<uint32_t>(q), a.cw_mul, a.cw_shift));
+        const int j = q - dp * Cw;
+        const int rel = base + dp * C + 64 * j;  // 0 <= rel < 64 * kTailChunks
+        const int from = rel >> 6, off = rel & 63;
+        const int len = min(64, C - 64 * j);
+        const uint64_t b0 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(bhi, from))) << 32) |
+                            static_cast<uint32_t>(__shfl(blo, from));
+        const uint64_t b1 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(bhi, from + 1))) << 32) |
+                            static_cast<uint32_t>(__shfl(blo, from + 1));
+        uint64_t word = b0 >> off;
+        if (off != 0)
+            word |= b1 << (64 - off);
+        if (len < 64)
+            word &= (uint64_t{1} << len) - 1;  // bits past the pixel's last channel are 0
+        if (l < count)
+            out[wA + l] = make_uint2(static_cast<uint32_t>(word), static_cast<uint32_t>(word >> 32));
+    }
 }
 
 // Fused batch-norm + shortcut + sign + bit-pack between two binary convolutions (Sec. 2.1.1 names
@@ -337,16 +386,32 @@ hipError_t launch_bitpack(const float* x, uint64_t* out, int64_t n_rows, int C, 
     uint2* o = reinterpret_cast<uint2*>(out);
     const bool flat = (C % 64) == 0;
     const int cw = static_cast<int>(Cw);
-    if (!flat && option(DABNN_OPT_BITPACK_ROWWISE) == 0) {  // test hook: the row-wise tail kernel
-        const int64_t per_block_t = static_cast<int64_t>(kTailWords) * kWavesPerBlock;
-        const int64_t blocks_t = (n_words + per_block_t - 1) / per_block_t;
+    const int tail_kernel = option(DABNN_OPT_BITPACK_ROWWISE);   // 0 by size, 1 row-wise, 2 64-bit flat stream
+    if (!flat && tail_kernel != 1) {
+        const int64_t n_floats = n_rows * C;
+        const int64_t per_block_t = int64_t{64} * kTailChunks * kWavesPerBlock;   // elements per workgroup
+        const int64_t blocks_t = (n_floats + per_block_t - 1) / per_block_t;
         if (blocks_t > 0x7fffffffLL)
             return hipErrorInvalidValue;
         const dim3 grid_t(static_cast<unsigned>(blocks_t));
-        if (sign_mode == 0)
-            bitpack_tail_kernel<0><<<grid_t, block, 0, stream>>>(xi, o, n_words, n_rows * C, C, cw);
-        else
-            bitpack_tail_kernel<1><<<grid_t, block, 0, stream>>>(xi, o, n_words, n_rows * C, C, cw);
+        TailArgs args{n_words, n_floats, C, cw, 0, 0, 0, 0};
+        division_constants(static_cast<uint32_t>(C), args.c_mul, args.c_shift);
+        division_constants(static_cast<uint32_t>(cw), args.cw_mul, args.cw_shift);
+        // 32-bit indices: the element count, rounded up to whole workgroups, below 2^32
+        const bool wide = tail_kernel == 2 || n_floats >= (int64_t{1} << 31);
+#define DABNN_LAUNCH(MODE, WIDE) bitpack_tail_kernel<MODE, WIDE><<<grid_t, block, 0, stream>>>(xi, o, args)
+        if (sign_mode == 0) {
+            if (wide)
+                DABNN_LAUNCH(0, true);
+            else
+                DABNN_LAUNCH(0, false);
+        } else {
+            if (wide)
+                DABNN_LAUNCH(1, true);
+            else
+                DABNN_LAUNCH(1, false);
+        }
+#undef DABNN_LAUNCH
         return hipGetLastError();
     }
     if (sign_mode == 0) {

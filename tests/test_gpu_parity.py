@@ -71,11 +71,13 @@ def test_bitpack_ragged(dabnn, oracle, C, n_pixels):
         assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
 
 
-def test_bitpack_rowwise_tail_kernel_forced(dabnn, oracle, option):
-    """Channel counts that are not multiples of 64 default to the flat-stream kernel; the row-wise
-    kernel of the same shapes through the library's option."""
-    option(dabnn.OPT_BITPACK_ROWWISE, 1)
-    for n_pixels, C in [(1, 1), (5, 3), (63, 65), (1025, 80), (64, 200), (77, 1000)]:
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_bitpack_other_tail_kernels_forced(dabnn, oracle, option, kernel):
+    """Channel counts that are not multiples of 64 default to the flat-stream kernel with 32-bit
+    indices; the row-wise kernel (1) and the flat-stream kernel with 64-bit indices (2, otherwise
+    used from 2^31 elements) on the same shapes through the library's option."""
+    option(dabnn.OPT_BITPACK_ROWWISE, kernel)
+    for n_pixels, C in [(1, 1), (5, 3), (63, 65), (1025, 80), (64, 200), (77, 1000), (4099, 129)]:
         x = wl.inject_zeros(wl.activations((n_pixels, C), 4300 + C), 4301 + C)
         for mode in (0, 1):
             assert np.array_equal(words(dabnn.bitpack(gpu(x), sign_mode=mode)), oracle.bitpack(x, mode))
@@ -83,12 +85,31 @@ def test_bitpack_rowwise_tail_kernel_forced(dabnn, oracle, option):
 
 @pytest.mark.parametrize("C", [1, 2, 31, 33, 63, 65, 96, 127, 129, 191, 320, 1000, 4097])
 def test_bitpack_flat_stream_tail_kernel(dabnn, oracle, C):
-    """Pixel counts around the 32-words-per-wavefront and 4-wavefronts-per-block boundaries."""
+    """Small word counts: one wavefront, the tensor ending inside its chunks."""
     Cw = (C + 63) // 64
     for n_words in (1, 31, 32, 33, 127, 128, 129, 4 * 32 * 7 + 5):
         n_pixels = max(1, n_words // Cw)
         x = wl.inject_zeros(wl.activations((n_pixels, C), 4400 + C + n_pixels), 4401 + C)
         assert np.array_equal(words(dabnn.bitpack(gpu(x))), oracle.bitpack(x)), (n_pixels, C)
+
+
+@pytest.mark.parametrize("kernel", [0, 2])
+@pytest.mark.parametrize("C", [1, 3, 31, 33, 65, 80, 127, 200, 4097])
+def test_bitpack_flat_stream_chunk_boundaries(dabnn, oracle, option, C, kernel):
+    """Element counts around the 2048 floats a wavefront owns and the 8192 of a workgroup (a
+    wavefront writes the words that start in its chunks: several passes of 64 for short rows),
+    with guard words around the output; 32-bit and 64-bit index variants."""
+    option(dabnn.OPT_BITPACK_ROWWISE, kernel)
+    Cw = (C + 63) // 64
+    for n_floats in (2047, 2048, 2049, 2048 + 64, 4096 + 63, 8191, 8192, 8193, 3 * 8192 + 2111, 70001):
+        n_pixels = max(1, n_floats // C)
+        x = wl.inject_zeros(wl.activations((n_pixels, C), 4500 + C + n_pixels), 4501 + C, frac=0.05)
+        for mode in (0, 1):
+            buf = torch.full((n_pixels * Cw + 16,), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+            out = buf[8:8 + n_pixels * Cw].view(n_pixels, Cw)
+            dabnn.bitpack(gpu(x), out=out, sign_mode=mode)
+            assert np.array_equal(words(out), oracle.bitpack(x, mode)), (n_pixels, C, mode)
+            assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
 
 
 def test_bitpack_special_values(dabnn, oracle):
