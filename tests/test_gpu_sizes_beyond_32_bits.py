@@ -62,9 +62,9 @@ def window_signs(a_words, hs, ws, H, W):
 
 def test_conv_with_tensors_above_4_gib(dabnn, oracle):
     """1 x 8200 x 8200 x 512 -> 16: 4.30 GB of packed activations, 4.30 GB of int32 output.  The
-    default route (not the activation-stationary family, whose offsets are 32-bit) and the
-    reference kernel, on sampled outputs: corners, edges, the rows whose byte offsets lie above
-    2^32, and random positions."""
+    default route (not the activation-stationary family, whose offsets are 32-bit), the
+    reference kernel and the fused threshold epilogue, on sampled outputs: corners, edges, the
+    rows whose byte offsets lie above 2^32, and random positions."""
     H = W = 8200
     Cin, Cout, Cw = 512, 16, 8
     assert dabnn.pick_algo(1, H, W, Cin, Cout, 3, 3, 1, 1) != dabnn.ALGO_AREG
@@ -79,7 +79,13 @@ def test_conv_with_tensors_above_4_gib(dabnn, oracle):
         ws += [0, 1, 4099, W - 1]
     hs = np.concatenate([np.array(hs), rng.integers(0, H, size=3000)])
     ws = np.concatenate([np.array(ws), rng.integers(0, W, size=3000)])
-    want = oracle.bconv2d_signed(window_signs(a_words, hs, ws, H, W), oracle.sign(wf), 1, 0)[:, 0, 0, :]
+    windows = window_signs(a_words, hs, ws, H, W)
+    want = oracle.bconv2d_signed(windows, oracle.sign(wf), 1, 0)[:, 0, 0, :]
+    gamma = rng.uniform(-1.5, 1.5, Cout).astype(np.float32)
+    beta = rng.normal(0, 0.5, Cout).astype(np.float32)
+    mean = rng.normal(0, 30.0, Cout).astype(np.float32)
+    var = rng.uniform(0.5, 40.0, Cout).astype(np.float32)
+    want_bits = oracle.bconv2d_bnsign(windows, wf, gamma, beta, mean, var, 1e-5, 1, 0)[:, 0, 0, :]
 
     a = torch.from_numpy(a_words.view(np.int64)).cuda().view(1, H, W, Cw)
     del a_words
@@ -92,3 +98,9 @@ def test_conv_with_tensors_above_4_gib(dabnn, oracle):
         got = y[0, hs_t, ws_t, :].cpu().numpy()
         del y
         assert np.array_equal(got, want), algo
+    # the fused threshold epilogue over the same activations (next-layer bits, Sec. 2.1.1)
+    print("fused threshold above 4 GiB", flush=True)
+    thr, flip = dabnn.bn_thresholds(gamma, beta, mean, var, 1e-5, 9 * Cin)
+    bits = dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, 1, 1)
+    assert bits.shape == (1, H, W, 1)
+    assert np.array_equal(bits[0, hs_t, ws_t, :].cpu().numpy().view(np.uint64), want_bits)
