@@ -39,8 +39,10 @@ static bool areg_offsets_fit(const ConvShape& s)
     const int64_t act_bytes = static_cast<int64_t>(s.N) * s.H * s.W * s.Cw * 8;
     const int64_t out_elems = static_cast<int64_t>(s.N) * s.Ho * s.Wo * s.Cout;
     const int64_t filter_bytes = static_cast<int64_t>(s.Cout) * 72 * s.Cw;
+    // (the transposed store addresses the 64 pixels of an output tile with a 32-bit byte offset)
+    const int64_t out_tile_bytes = static_cast<int64_t>(s.Cout) * 64 * 4;
     return act_bytes < (int64_t{1} << 32) && out_elems < (int64_t{1} << 31) &&
-           filter_bytes < (int64_t{1} << 32);
+           filter_bytes < (int64_t{1} << 32) && out_tile_bytes < (int64_t{1} << 32);
 }
 
 static bool areg_geometry(const ConvShape& s)

@@ -339,8 +339,9 @@ bool bgemm_rowreg_supports(int64_t M, int N, int Kw, const void* C)
         default:
             return false;
     }
-    // 32-bit byte offsets into A, 16-byte stores into C
+    // 32-bit byte offsets into A and into a 64-row tile of C, 16-byte stores into C
     return N % 16 == 0 && M * Kw * 8 < (int64_t{1} << 32) &&
+           static_cast<int64_t>(N) * 64 * 4 < (int64_t{1} << 32) &&
            (reinterpret_cast<uintptr_t>(C) & 15) == 0;
 }
 

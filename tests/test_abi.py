@@ -96,6 +96,17 @@ def test_tensors_past_the_32bit_byte_offsets_leave_the_activation_stationary_fam
     # just below the limit the family is still used: 8192 x 8191 x 8 words x 8 B < 2^32
     assert lib.dabnn_bconv2d_pick_algo(1, 8192, 8191, 512, 16, 3, 3, 1, 1) == AREG
     assert lib.dabnn_bconv2d_pick_algo(1, 8192, 8192, 512, 16, 3, 3, 1, 1) != AREG
+    # the 64 pixels of an output tile are addressed with a 32-bit byte offset too: 64 * Cout * 4 < 2^32
+    assert lib.dabnn_bconv2d_pick_algo(1, 8, 8, 64, (1 << 24) - 16, 3, 3, 1, 1) == AREG
+    assert lib.dabnn_bconv2d_pick_algo(1, 8, 8, 64, 1 << 24, 3, 3, 1, 1) not in (AREG, -1)
+
+
+def test_bgemm_route_stops_where_an_output_tile_passes_32bit_byte_offsets(lib):
+    """The BGEMM kernel (here through a 1x1 convolution) addresses the 64 rows of an output tile
+    with 32-bit byte offsets: 64 rows of N int32 must stay below 4 GiB."""
+    BGEMM = 4
+    assert lib.dabnn_bconv2d_pick_algo(1, 1, 64, 64, (1 << 24) - 16, 1, 1, 1, 0) == BGEMM
+    assert lib.dabnn_bconv2d_pick_algo(1, 1, 64, 64, 1 << 24, 1, 1, 1, 0) not in (BGEMM, -1)
 
 
 def test_every_word_count_has_a_tuned_kernel(lib):
