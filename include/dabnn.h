@@ -59,10 +59,11 @@ typedef enum {
                                  on, a quarter of it) in VGPRs, weights are broadcast through SGPRs; 3x3
                                  kernels, stride 1 or 2, any Cin; Cout % 4 == 0 (% 8 for an odd number of
                                  words per pixel, % 16 above 8 words), y 16-byte aligned, packed
-                                 activations below 4 GiB */
+                                 activations and packed filters below 4 GiB, the output below 2^31
+                                 elements, Cout below 2^24 */
     DABNN_ALGO_BGEMM = 4      /* 1x1, stride 1, pad 0 only: the convolution IS the BGEMM of Eq. 1;
-                                 Cout % 16 == 0, y 16-byte aligned, row lengths dabnn_bgemm's
-                                 fast kernel supports */
+                                 Cout % 16 == 0 and below 2^24, y 16-byte aligned, packed activations
+                                 below 4 GiB, row lengths dabnn_bgemm's fast kernel supports */
 } dabnn_algo;
 
 typedef enum {
