@@ -114,6 +114,15 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_kernel(
     // 64 pixels x TR channels of int32 per wavefront, used only by the transposed store
     __shared__ int32_t tile_lds[TR > 0 ? 4 * 64 * TR : (is_res(TR) ? 4 * 64 * AregGeom<CW, TR>::CG : 4)];
 
+    // The kernel-argument segment spans three cache lines, and the first window load reads the
+    // first of them only after the launch geometry (in the other two) has arrived and been
+    // used: request it now, so that a launch starts with one memory round trip, not two.
+    {
+        const uint64_t ka_addr = reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr());
+        const uint32_t first_line =
+            *reinterpret_cast<const uint32_t __attribute__((address_space(4)))*>(ka_addr);
+        asm volatile("" : : "s"(first_line));
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gw = blockIdx.x * 4 + wave;

@@ -36,10 +36,11 @@ __device__ __forceinline__ void schedule_fence()
 // which selects the identity).
 __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t shift)
 {
-    if (shift == 32)
-        return n;
+    // a select, not a branch: a branch on a constant that was just loaded makes every caller
+    // wait for that load before it may even request what it needs next
     const uint32_t t = __umulhi(mul, n);
-    return (t + ((n - t) >> 1)) >> shift;
+    const uint32_t q = (t + ((n - t) >> 1)) >> (shift & 31);
+    return shift == 32 ? n : q;
 }
 
 // Constants of fast_div for the divisor d >= 1.
