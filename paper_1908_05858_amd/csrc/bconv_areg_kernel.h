@@ -484,6 +484,12 @@ hipError_t launch_areg_inst(const uint32_t* a, const uint32_t* w, int32_t* y, co
     // the SIMDs' shares equal.
     const int simds = device_cu_count() * 4;
     int64_t per_simd = std::max(7, blocks_per_cu + 3);
+    // A launch with less than 20 groups per SIMD: 7 ranges per SIMD whatever fits at once.  Ten
+    // ranges of one or two groups each make the SIMDs' shares uneven and every range pays its
+    // window load (measured, 12 groups per SIMD at one word per pixel: 64x56x56x64->64 17.7 us
+    // against 20.8, 128x56x56x64->128 stride 2 17.1 against 19.2; no difference from 24 up).
+    if (n_groups < 20 * simds)
+        per_simd = 7;
     if (option(DABNN_OPT_AREG_RANGES_PER_SIMD) > 0)
         per_simd = option(DABNN_OPT_AREG_RANGES_PER_SIMD);
     if (per_simd * simds > n_groups)
