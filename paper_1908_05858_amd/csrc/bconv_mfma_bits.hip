@@ -296,11 +296,12 @@ __global__ __launch_bounds__(256) void bconv_mfma_bits_kernel(const uint32_t* __
                 }
             }
         }
-        // With the fused epilogue the compiler otherwise moves the matrix instructions past all
-        // later stages (towards the compares that use their results) and keeps every operand of
-        // the whole K loop alive: an empty statement that "uses" the accumulators keeps the
-        // instructions of a stage inside the stage.
-        if constexpr (BITS) {
+        // With the fused epilogue (and with the masked stores of the tiny-input variant) the
+        // compiler otherwise moves the matrix instructions past all later stages, towards the
+        // compares that use their results, and keeps every operand of the whole K loop alive: an
+        // empty statement that "uses" the accumulators keeps the instructions of a stage inside
+        // the stage.
+        if constexpr (BITS || MASKED) {
 #pragma unroll
             for (int i = 0; i < MB; ++i)
 #pragma unroll
