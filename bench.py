@@ -538,14 +538,23 @@ def widened_rows(result, args, binding, wl, np, torch, layers, N, xs, acts, wps,
                 binding.bconv2d_bn_residual(a_in, wps[li], scales[li], sh1[li], r, L.Cin, L.stride, 1,
                                             x_out=z1[li], out=b1[li])
                 a_in = b1[li]
-        eager_us = wall_ms(one_image, 200) * 1e3
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            one_image()
+        # Small launches take the call's two-kernel route (less device time, one launch more):
+        # both routes, issued eagerly from this process (bound by the host's launch cost) and
+        # replayed from a HIP graph (device time).
+        lat = {}
+        for name, route in (("", 0), ("_one_kernel_route", 1)):
+            binding.set_option(binding.OPT_RES_FUSED, route)
+            lat["eager_us" + name] = round(wall_ms(one_image, 200) * 1e3, 1)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                one_image()
+            lat["hip_graph_replay_us" + name] = round(wall_ms(graph.replay, 200) * 1e3, 1)
+            del graph
+        binding.set_option(binding.OPT_RES_FUSED, 0)
         result["batch1_chain_latency"] = {
-            "what": "16 dependent blocks (dabnn_bconv2d_bn_residual) on one 224x224 image's feature maps",
-            "eager_us": round(eager_us, 1), "hip_graph_replay_us": round(wall_ms(graph.replay, 200) * 1e3, 1)}
-        del graph
+            "what": "16 dependent blocks (dabnn_bconv2d_bn_residual) on one 224x224 image's feature maps; the "
+                    "library's choice for launches this small (convolution + layer kernel) and, forced, the "
+                    "one-kernel route of the larger batches", **lat}
 
     # Comparison row: the same convolutions on the int8 matrix cores with every bit expanded to a
     # +-1 byte (dabnn_expand_int8 + dabnn_bconv2d_int8).  One step = 16 x (expand the packed

@@ -94,7 +94,9 @@ typedef enum {
                                       words, 4 also at 4 words, 8 at 8 words whatever the launch's size */
     DABNN_OPT_AREG_RANGES_PER_SIMD = 8, /* n > 0: cut the work of a DABNN_ALGO_AREG launch into n ranges per SIMD */
     DABNN_OPT_MFMA_PIXEL_BLOCKS = 9, /* dabnn_bconv2d_mfma: 2 or 4 blocks of 32 pixels per wavefront */
-    DABNN_OPT_COUNT = 10
+    DABNN_OPT_RES_FUSED = 10,      /* dabnn_bconv2d_bn_residual: 1 the one-kernel route wherever it applies (by
+                                      default not for small launches), 2 always convolution + layer kernel */
+    DABNN_OPT_COUNT = 11
 } dabnn_option;
 
 /* Sets option `option` (a dabnn_option) to `value` and returns DABNN_OK, or DABNN_ERR_UNSUPPORTED
@@ -167,8 +169,10 @@ int dabnn_bn_sign_pack(const int32_t *y, const float *scale, const float *shift,
  *                  int32 result for shapes the fused kernel does not cover); must not alias r
  *                  (dabnn_bn_sign_pack allows x_out == r; this call does not)
  *   bits         : u64 [N][Ho][Wo][ceil(Cout/64)] device, tail bits 0
- * The fused kernel runs 3x3 kernels, stride 1 or 2, ceil(Cin/64) in {1,2,4,8}, Cout % 64 == 0,
- * a shortcut, and scale, shift, r, x_out 16-byte aligned; every other valid case runs as the two kernels in sequence.
+ * The fused kernel runs 3x3 kernels, stride 1 or 2, up to 8 words per pixel (Cin <= 512), Cout % 64 == 0,
+ * a shortcut, and scale, shift, r, x_out 16-byte aligned; every other valid case, and a launch with
+ * fewer than about two 16-channel groups of work per SIMD (a single image, a small batch), runs as
+ * the two kernels in sequence.
  */
 int dabnn_bconv2d_bn_residual(const uint64_t *a, const uint64_t *w, const float *scale,
                               const float *shift, const float *r, float *x_out, uint64_t *bits,

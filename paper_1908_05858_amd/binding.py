@@ -75,7 +75,8 @@ EXPORTS = ["dabnn_packed_words", "dabnn_conv_out_dim", "dabnn_bitpack", "dabnn_p
            "dabnn_prepare_weights_mfma", "dabnn_bconv2d_mfma", "dabnn_bconv2d_bnsign_mfma"]
 
 (OPT_AREG_SLOTS, OPT_AREG_TAIL, OPT_AREG_STORE, OPT_RES_CHANNELS, OPT_WREG_PIXELS, OPT_BGEMM_COLUMNS,
- OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD, OPT_MFMA_PIXEL_BLOCKS) = range(10)
+ OPT_BITPACK_ROWWISE, OPT_AREG_SPLIT, OPT_AREG_RANGES_PER_SIMD, OPT_MFMA_PIXEL_BLOCKS,
+ OPT_RES_FUSED) = range(11)
 
 
 def set_option(option, value):

@@ -101,6 +101,14 @@ hipError_t launch_bconv_bn_residual_areg(const uint64_t* a, const uint64_t* w, c
 #undef DABNN_CASE
 }
 
+bool bconv_areg_small_launch(const ConvShape& s)
+{
+    // fewer than 2 (one word per pixel) or 2.5 sixteen-channel groups per SIMD
+    const int64_t tiles = (static_cast<int64_t>(s.N) * s.Ho * s.Wo + 63) / 64;
+    const int64_t simds = static_cast<int64_t>(device_cu_count()) * 4;
+    return tiles * (s.Cout / 16) * 4 < simds * (s.Cw == 1 ? 8 : 10);
+}
+
 bool bconv_areg_supports(const ConvShape& s, const void* y)
 {
     if (!areg_geometry(s) || (reinterpret_cast<uintptr_t>(y) & 15) != 0)

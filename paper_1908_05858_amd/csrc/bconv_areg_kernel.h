@@ -544,9 +544,7 @@ hipError_t launch_areg_s(const uint32_t* a, const uint32_t* w, int32_t* y, const
     // as many wavefronts.  Measured by HIP-graph replay, direct against transposed: 14x14x256->256
     // at batch 1: 4.4 against 8.9 us, at batch 32: 11.8 against 16.3; 56x56x64->64 at batch 8: 6.1
     // against 7.3, at batch 12 (2.3 groups per SIMD): 7.3 against 6.7.
-    const int64_t tiles = (static_cast<int64_t>(s.N) * s.Ho * s.Wo + 63) / 64;
-    const int64_t simds = static_cast<int64_t>(device_cu_count()) * 4;
-    if (tr == 16 && tiles * (s.Cout / 16) * 4 < simds * (CW == 1 ? 8 : 10))
+    if (tr == 16 && bconv_areg_small_launch(s))
         tr = 0;
     const int forced = option(DABNN_OPT_AREG_STORE);  // 0 as above, 1 direct, 16 transposed
     if (forced == 1)

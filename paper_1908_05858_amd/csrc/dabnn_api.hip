@@ -425,7 +425,13 @@ int dabnn_bconv2d_bn_residual(const uint64_t* a, const uint64_t* w, const float*
         !aligned(r, 4) || !aligned(x_out, 4) || !aligned(bits, 8))
         return DABNN_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dabnn::bconv_bn_residual_areg_supports(s, scale, shift, r, x_out)) {
+    // The one-kernel route works in 16- or 32-channel groups.  A small launch (a single image, a
+    // small batch) is bound by the latency of those groups; the convolution with its short
+    // direct-store groups followed by the layer kernel is faster there (one image through the 16
+    // Bi-Real-18 blocks: 100 against 142 us of device time; level at batch 16).
+    const int route = dabnn::option(DABNN_OPT_RES_FUSED);   // 0 by size, 1 one kernel, 2 two kernels
+    const bool one_kernel = route == 1 || (route == 0 && !dabnn::bconv_areg_small_launch(s));
+    if (one_kernel && dabnn::bconv_bn_residual_areg_supports(s, scale, shift, r, x_out)) {
         const hipError_t e =
             dabnn::launch_bconv_bn_residual_areg(a, w, scale, shift, r, x_out, bits, s, st);
         return e == hipSuccess ? DABNN_OK : DABNN_ERR_LAUNCH;

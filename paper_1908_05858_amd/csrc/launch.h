@@ -80,5 +80,8 @@ bool bconv_bn_residual_areg_supports(const ConvShape& s, const void* scale, cons
 bool bconv_bnsign_areg_supports(const ConvShape& s);
 bool bconv_wreg_supports(const ConvShape& s);
 bool bconv_areg_supports(const ConvShape& s, const void* y);
+// A launch with only a few 16-channel groups per SIMD (a single image, a small batch): bound by the
+// latency of its groups, not by throughput.
+bool bconv_areg_small_launch(const ConvShape& s);
 
 }  // namespace dabnn

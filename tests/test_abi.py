@@ -128,7 +128,7 @@ def test_options(lib):
     """Options default to 0, are set and read back through the C ABI, and unknown ones are refused;
     the library ignores the environment."""
     import os
-    n_options = 10
+    n_options = 11
     text = open(os.path.join(ROOT, "include", "dabnn.h")).read()
     assert f"DABNN_OPT_COUNT = {n_options}" in text
     for opt in range(n_options):

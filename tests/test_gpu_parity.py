@@ -180,11 +180,18 @@ RESIDUAL_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
 ]
 
 
+@pytest.mark.parametrize("route", [0, 1, 2], ids=["by-size", "one-kernel", "two-kernels"])
 @pytest.mark.parametrize("with_r", [True, False])
 @pytest.mark.parametrize("shape", RESIDUAL_SHAPES, ids=lambda s: "-".join(map(str, s)))
-def test_bconv2d_bn_residual(dabnn, oracle, shape, with_r):
+def test_bconv2d_bn_residual(dabnn, oracle, option, shape, with_r, route):
     """One call against the oracle's convolution followed by the oracle's BN + shortcut + sign +
-    pack layer; z compared bit for bit."""
+    pack layer; z compared bit for bit.  Small launches default to the two-kernel route, so the
+    one-kernel route is also forced (where the shape has one) and so is the other."""
+    option(dabnn.OPT_RES_FUSED, route)
+    check_bn_residual(dabnn, oracle, shape, with_r)
+
+
+def check_bn_residual(dabnn, oracle, shape, with_r):
     N, H, W, Cin, Cout, k, stride, pad = shape
     print("residual", shape, with_r, flush=True)
     seed = 7000 + sum(shape)
@@ -206,16 +213,18 @@ def test_bconv2d_bn_residual(dabnn, oracle, shape, with_r):
 @pytest.mark.parametrize("slots", [1, 5, 64])
 def test_bconv2d_bn_residual_work_split(dabnn, oracle, slots, option):
     option(dabnn.OPT_AREG_SLOTS, slots)
-    test_bconv2d_bn_residual(dabnn, oracle, (2, 14, 14, 128, 128, 3, 1, 1), True)
-    test_bconv2d_bn_residual(dabnn, oracle, (3, 9, 7, 64, 192, 3, 2, 1), False)
+    option(dabnn.OPT_RES_FUSED, 1)
+    check_bn_residual(dabnn, oracle, (2, 14, 14, 128, 128, 3, 1, 1), True)
+    check_bn_residual(dabnn, oracle, (3, 9, 7, 64, 192, 3, 2, 1), False)
 
 
 def test_bconv2d_bn_residual_sixteen_channel_groups_forced(dabnn, oracle, option):
     """One-word-per-pixel layers default to 32-channel groups in the fused block kernel; the
     16-channel variant of the same shapes through the library's option."""
     option(dabnn.OPT_RES_CHANNELS, 16)
+    option(dabnn.OPT_RES_FUSED, 1)
     for shape in [(1, 14, 14, 64, 64, 3, 1, 1), (5, 57, 30, 64, 64, 3, 1, 1), (3, 11, 10, 64, 128, 3, 2, 1)]:
-        test_bconv2d_bn_residual(dabnn, oracle, shape, True)
+        check_bn_residual(dabnn, oracle, shape, True)
 
 
 def test_bconv2d_bn_residual_full_batch_layer(dabnn, oracle):
@@ -948,9 +957,10 @@ def test_random_shapes_every_entry_point(dabnn, oracle, shape):
         assert np.array_equal(y8.cpu().numpy(), want)
 
 
-def test_results_are_identical_run_to_run(dabnn):
+def test_results_are_identical_run_to_run(dabnn, option):
     """Integer outputs and packed words must not depend on scheduling: five runs of every tuned
     kernel family on a shape that spans many wavefronts, compared byte for byte."""
+    option(dabnn.OPT_RES_FUSED, 1)   # the one-kernel block route, whatever the launch's size
     x = gpu(wl.activations((16, 28, 28, 128), 8800))
     wf = gpu(wl.weights((128, 3, 3, 128), 8801))
     gamma, beta, mean, var = _bn_params(128, 8802)
