@@ -60,8 +60,8 @@ def main():
                          "HBM traffic) so that counter runs under rocprofv3 --pmc can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; batch sharding across GPUs is a design note "
-              "only (see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path would shard by batch: every image is "
+              "independent and the packed weights are replicated). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -345,7 +345,8 @@ def main():
 
 
 def other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle):
-    """Benchmark configs[0..3]: per launch microseconds (median of 20 HIP-event intervals),
+    """The other four benchmark configurations (single conv, stride-1 sweep, bit-pack shapes,
+    stride-2 layers): per launch microseconds (median of 20 HIP-event intervals),
     throughput, roofline fraction, and the oracle's wall time for the same tensors on the host.
     A short launch (below 40 us) is of the order of what the host takes to issue it from Python
     and of what an event pair adds, so it is timed as 20 launches replayed from a HIP graph (the
