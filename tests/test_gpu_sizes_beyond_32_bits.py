@@ -3,8 +3,8 @@
 The tuned kernels index with 32-bit offsets where that is enough and the dispatcher routes larger
 tensors to kernels that index with 64 bits (Sec. 2.1.1 and 2.1.2 state the operations for any
 size).  These cases are the only ones that run those routes at sizes where a 32-bit offset
-would wrap: a bit-pack of more than 2^31 elements (both kernels) and a convolution whose packed
-activations and whose output are larger than 4 GiB each.
+would wrap: a bit-pack of more than 2^31 elements (both kernels), a convolution whose packed
+activations and whose output are larger than 4 GiB each, and a BGEMM with such an A and C.
 """
 import numpy as np
 import pytest
@@ -104,3 +104,29 @@ def test_conv_with_tensors_above_4_gib(dabnn, oracle):
     bits = dabnn.bconv2d_bnsign(a, wp, thr, flip, Cin, 1, 1)
     assert bits.shape == (1, H, W, 1)
     assert np.array_equal(bits[0, hs_t, ws_t, :].cpu().numpy().view(np.uint64), want_bits)
+
+
+def row_signs(words):
+    """+-1 floats [S, 64*Kw] of packed rows [S, Kw]: bit 1 is -1, LSB first."""
+    bits = np.unpackbits(np.ascontiguousarray(words).view(np.uint8), axis=-1, bitorder="little")
+    return 1.0 - 2.0 * bits.astype(np.float32)
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["signed", "matches"])
+def test_bgemm_with_matrices_above_4_gib(dabnn, oracle, mode):
+    """Eq. 1 with A = 70,000,001 rows of 8 words (4.48 GB: past the fast kernel's 32-bit byte
+    offsets, so the kernel that indexes with 64 bits runs) and 16 columns (4.48 GB of output):
+    sampled rows, among them the first, the last and those around byte offset 2^32."""
+    M, Kw, N = 70_000_001, 8, 16
+    rng = np.random.default_rng(7300)
+    A = rng.integers(0, 1 << 64, size=(M, Kw), dtype=np.uint64)
+    B = rng.integers(0, 1 << 64, size=(N, Kw), dtype=np.uint64)
+    wrap = (1 << 32) // (8 * Kw)                       # the row whose byte offset in A (and C) is 2^32
+    rows = np.concatenate([np.array([0, 1, M - 2, M - 1, wrap - 1, wrap, wrap + 1]),
+                           rng.integers(0, M, size=3000)])
+    want = oracle.bgemm_signed(row_signs(A[rows]), row_signs(B), mode)
+    Ag = torch.from_numpy(A.view(np.int64)).cuda()
+    del A
+    C = dabnn.bgemm(Ag, torch.from_numpy(B.view(np.int64)).cuda(), 64 * Kw, mode=mode)
+    assert C.shape == (M, N)
+    assert np.array_equal(C[torch.from_numpy(rows).cuda()].cpu().numpy(), want)
