@@ -151,12 +151,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
             return fast_div(B, a.c_mul, a.c_shift);
     };
     const index_t pA = pixel_of(B0);
-    const int jA = (static_cast<int>(B0 - pA * C) + 63) >> 6;   // <= Cw: then it is (pA + 1, 0)
+    const int jA = static_cast<int>((static_cast<uint32_t>(B0 - pA * C) + 63u) >> 6);   // <= Cw: then it is (pA + 1, 0)
     const index_t wA = pA * Cw + jA;
     index_t wB = n_words;
     if (B0 + 64 * kTailChunks < n_floats) {
         const index_t pB = pixel_of(B0 + 64 * kTailChunks);
-        wB = pB * Cw + ((static_cast<int>(B0 + 64 * kTailChunks - pB * C) + 63) >> 6);
+        wB = pB * Cw + ((static_cast<uint32_t>(B0 + 64 * kTailChunks - pB * C) + 63u) >> 6);
     }
     const int count = static_cast<int>(wB - wA);   // words that start in these chunks
 
@@ -186,15 +186,18 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void bitpack_tail_kernel(
 
     // lane l assembles word wA + l (+ 64 per further pass), in 32-bit arithmetic relative to the
     // first chunk: flat bit of pixel pA minus B0 (negative when the pixel starts before the chunk)
-    const int base = -static_cast<int>(B0 - pA * C);
+    // (unsigned arithmetic: the terms can approach 2^31 for rows of a billion channels, their sum
+    // is below 2048)
+    const uint32_t base = 0u - static_cast<uint32_t>(B0 - pA * C);
     // (every lane takes part in the lane exchange of every pass; only the store is conditional)
     for (int first = 0; first < count; first += 64) {
         const int l = first + lane;
         const int q = jA + min(l, count - 1);   // word index counted from pixel pA's first word
         const int dp = static_cast<int>(fast_div(static_cast<uint32_t>(q), a.cw_mul, a.cw_shift));
         const int j = q - dp * Cw;
-        const int rel = base + dp * C + 64 * j;  // 0 <= rel < 64 * kTailChunks
-        const int from = rel >> 6, off = rel & 63;
+        const uint32_t rel = base + static_cast<uint32_t>(dp) * static_cast<uint32_t>(C) +
+                             64u * static_cast<uint32_t>(j);  // 0 <= rel < 64 * kTailChunks
+        const int from = static_cast<int>(rel >> 6), off = static_cast<int>(rel & 63);
         const int len = min(64, C - 64 * j);
         const uint64_t b0 = (static_cast<uint64_t>(static_cast<uint32_t>(__shfl(bhi, from))) << 32) |
                             static_cast<uint32_t>(__shfl(blo, from));

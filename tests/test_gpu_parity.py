@@ -112,6 +112,15 @@ def test_bitpack_flat_stream_chunk_boundaries(dabnn, oracle, option, C, kernel):
             assert torch.all(buf[:8] == 0x5A5A5A5A5A5A5A5A) and torch.all(buf[-8:] == 0x5A5A5A5A5A5A5A5A)
 
 
+@pytest.mark.parametrize("kernel", [0, 1, 2])
+def test_bitpack_very_long_rows(dabnn, oracle, option, kernel):
+    """Rows much longer than what a wavefront covers (a million channels, not a multiple of 64)."""
+    option(dabnn.OPT_BITPACK_ROWWISE, kernel)
+    x = wl.inject_zeros(wl.activations((3, 1_000_003), 4600), 4601)
+    for mode in (0, 1):
+        assert np.array_equal(words(dabnn.bitpack(gpu(x), sign_mode=mode)), oracle.bitpack(x, mode))
+
+
 def test_bitpack_special_values(dabnn, oracle):
     row = wl.special_values()
     x = np.tile(row, (3, 13))[:, :200].copy()       # C = 200: specials in every word, with a tail
