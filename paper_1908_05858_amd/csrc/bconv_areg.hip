@@ -29,6 +29,9 @@ DABNN_DECLARE_BOTH(5) DABNN_DECLARE_BOTH(6) DABNN_DECLARE_BOTH(7) DABNN_DECLARE_
                                   hipStream_t stream);
 DABNN_DECLARE_SPLIT(1) DABNN_DECLARE_SPLIT(2) DABNN_DECLARE_SPLIT(3) DABNN_DECLARE_SPLIT(4)
 #undef DABNN_DECLARE_SPLIT
+hipError_t launch_split_bits_cw2(const uint32_t* a, const uint32_t* w, uint64_t* out,
+                                 const int32_t* thr, const uint64_t* flip, const ConvShape& s,
+                                 hipStream_t stream);
 
 // The kernels address a window tap as the tensor base plus a 32-bit BYTE offset, and (on the
 // direct-store path) the output with 32-bit element offsets: the packed activation tensor must
@@ -60,6 +63,20 @@ static bool areg_geometry(const ConvShape& s)
         default: return hipErrorNotSupported;                         \
     }
 
+// 8 words per pixel: the four-wavefront kernel or the one-wavefront kernel?
+static bool use_split_at_8_words(const ConvShape& s)
+{
+    const int split_option = option(DABNN_OPT_AREG_SPLIT);
+    if (s.Cout % 16 != 0 || option(DABNN_OPT_AREG_STORE) == 1 || split_option == 1)
+        return false;
+    // A latency-bound launch at 8 words (fewer than 3 groups per CU) is shorter with the
+    // one-wavefront kernel's groups of 4 channels: 7x7x512->512 at batch 1 6.8 against 8.1 us, at
+    // batch 24 11.7 against 13.9, at batch 32 13.7 against 13.0.
+    const int64_t tiles = (static_cast<int64_t>(s.N) * s.Ho * s.Wo + 63) / 64;
+    const bool few_groups = tiles * (s.Cout / 16) < 3 * static_cast<int64_t>(device_cu_count());
+    return !few_groups || split_option == 8;
+}
+
 bool bconv_bnsign_areg_supports(const ConvShape& s)
 {
     return areg_geometry(s) && s.Cw <= 8 && s.Cout % 64 == 0;
@@ -74,6 +91,10 @@ hipError_t launch_bconv_bnsign_areg(const uint64_t* a, const uint64_t* w, const 
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
     const uint2* f2 = reinterpret_cast<const uint2*>(flip);
+    // 8 words per pixel: the four-wavefront kernel, as for the plain convolution (7x7x512->512
+    // at batch 256: 58 against 68 us), unless the launch is small or the option says otherwise
+    if (s.Cw == 8 && use_split_at_8_words(s))
+        return launch_split_bits_cw2(a32, w32, out, thr, flip, s, stream);
 #define DABNN_CASE(CW, S) return launch_bits_cw##CW##_s##S(a32, w32, out, s, stream, thr, f2)
     DABNN_SWITCH_CW_S(s, DABNN_CASE)
 #undef DABNN_CASE
@@ -132,13 +153,8 @@ hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, c
     // Option DABNN_OPT_AREG_SPLIT: 4 forces it for 4 words as well, 1 never uses it below 9 words.
     const int split_option = option(DABNN_OPT_AREG_SPLIT);
     const bool split_fits = s.Cw % 4 == 0 && s.Cout % 16 == 0 && option(DABNN_OPT_AREG_STORE) != 1;
-    // A latency-bound launch at 8 words (fewer than 3 groups per CU) is shorter with the
-    // one-wavefront kernel's groups of 4 channels: 7x7x512->512 at batch 1 6.8 against 8.1 us, at
-    // batch 24 11.7 against 13.9, at batch 32 13.7 against 13.0.
-    const int64_t tiles = (static_cast<int64_t>(s.N) * s.Ho * s.Wo + 63) / 64;
-    const bool few_groups = tiles * (s.Cout / 16) < 3 * static_cast<int64_t>(device_cu_count());
-    const bool use_split = s.Cw > 8 || (split_fits && split_option != 1 &&
-                                        ((s.Cw == 8 && (!few_groups || split_option == 8)) || split_option == 4));
+    const bool use_split = s.Cw > 8 || (s.Cw == 8 && use_split_at_8_words(s)) ||
+                           (split_fits && split_option == 4);
     if (!use_split) {
 #define DABNN_CASE(CW, S) return launch_areg_cw##CW##_s##S(a32, w32, y, s, stream)
         DABNN_SWITCH_CW_S(s, DABNN_CASE)

@@ -4,4 +4,13 @@
 
 namespace dabnn {
 DABNN_DEFINE_SPLIT_ENTRY_POINT(2, )
+
+// 8 words per pixel with the fused threshold epilogue: one launch covers all words.
+hipError_t launch_split_bits_cw2(const uint32_t* a, const uint32_t* w, uint64_t* out,
+                                 const int32_t* thr, const uint64_t* flip, const ConvShape& s,
+                                 hipStream_t stream)
+{
+    const SplitLaunch L{a, w, reinterpret_cast<int32_t*>(out), 8, 0, true, 4, thr, flip};
+    return launch_split_inst<2, false, true>(L, s, stream);
+}
 }  // namespace dabnn

@@ -40,6 +40,8 @@ struct SplitArgs {
     int groups_per_tile;               // Cout / 16
     int n_groups, base_groups, rem_groups;   // work split over the workgroups of the launch
     int n_active;                      // PARTIAL: wavefronts that have words to read
+    const int32_t* thr;                // BITS: per-channel thresholds and flip bits of the fused
+    const uint64_t* flip;              //       threshold epilogue (y is then the packed output)
 };
 
 template <int CWC>
@@ -95,7 +97,12 @@ __device__ __forceinline__ void split_compute_unit(const uint32_t (&sb)[SB], int
                         &sb[2 * kDC + 3], &sb[3 * kDC + 3]);
 }
 
-template <int CWC, bool PARTIAL>
+// BITS: the fused threshold epilogue of dabnn_bconv2d_bnsign for a launch that covers all words of
+// a pixel.  Instead of y the kernel writes the next layer's packed activations, bit c of a pixel
+// = (y < thr[c]) XOR flip bit c: after the reduction lane (P, j) holds channels 4j..4j+3 of pixel
+// P, forms their four bits, the four lanes of a pixel OR theirs together (two DPP quad permutes)
+// and one of them stores the group's 16 bits.
+template <int CWC, bool PARTIAL, bool BITS = false>
 __global__ __launch_bounds__(256) void bconv3x3_areg_split_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     const SplitArgs p)
@@ -240,7 +247,19 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_split_kernel(
         o.y = finish_output(d.y, k_term);
         o.z = finish_output(d.z, k_term);
         o.w = finish_output(d.w, k_term);
-        if (tile * 64 + P < q->total_pix) {
+        if constexpr (BITS) {
+            const int4 t = *reinterpret_cast<const int4*>(q->thr + cgi * CG + 4 * j);
+            uint32_t nib = (o.x < t.x ? 1u : 0u) | (o.y < t.y ? 2u : 0u) | (o.z < t.z ? 4u : 0u) |
+                           (o.w < t.w ? 8u : 0u);
+            nib <<= 4 * j;
+            // OR over the four lanes of the pixel (lanes 4q..4q+3): xor-1 then xor-2 partners
+            nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0xB1, 0xF, 0xF, true));
+            nib |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(nib), 0x4E, 0xF, 0xF, true));
+            const uint32_t fl16 = static_cast<uint32_t>(q->flip[cgi >> 2] >> (16 * (cgi & 3))) & 0xffffu;
+            if (tile * 64 + P < q->total_pix && j == 0)
+                reinterpret_cast<uint16_t*>(y)[static_cast<size_t>(tile * 64 + P) * (q->Cout >> 4) + cgi] =
+                    static_cast<uint16_t>(nib ^ fl16);
+        } else if (tile * 64 + P < q->total_pix) {
             int32_t* dst = y + static_cast<size_t>(tile * 64 + P) * q->Cout + cgi * CG + 4 * j;
             if (q->accumulate) {
                 const int4 old = *reinterpret_cast<const int4*>(dst);
@@ -270,12 +289,14 @@ struct SplitLaunch {
     int word0;
     bool first;          // writes y = K - 2*P; otherwise adds -2*P to y
     int active_waves;    // 4, or 1..3 with PARTIAL
+    const int32_t* thr = nullptr;    // BITS: thresholds and flip bits; y is the packed output
+    const uint64_t* flip = nullptr;
 };
 
-template <int CWC, bool PARTIAL>
+template <int CWC, bool PARTIAL, bool BITS = false>
 hipError_t launch_split_inst(const SplitLaunch& L, const ConvShape& s, hipStream_t stream)
 {
-    auto kernel = bconv3x3_areg_split_kernel<CWC, PARTIAL>;
+    auto kernel = bconv3x3_areg_split_kernel<CWC, PARTIAL, BITS>;
     static const int blocks_per_cu = resident_blocks_per_cu(kernel);
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 63) / 64;
@@ -320,6 +341,8 @@ hipError_t launch_split_inst(const SplitLaunch& L, const ConvShape& s, hipStream
     p.base_groups = n_groups / static_cast<int>(blocks);
     p.rem_groups = n_groups % static_cast<int>(blocks);
     p.n_active = L.active_waves;
+    p.thr = L.thr;
+    p.flip = L.flip;
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
                        L.a + 2 * L.word0, L.w + 2 * L.word0, L.y, p);
     return hipGetLastError();

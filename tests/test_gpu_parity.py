@@ -774,6 +774,16 @@ def test_bconv2d_bnsign(dabnn, oracle, shape):
                              f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}")
 
 
+@pytest.mark.parametrize("shape", [(9, 7, 7, 512, 512, 3, 1, 1), (3, 14, 14, 512, 192, 3, 2, 1),
+                                   (1, 5, 13, 512, 64, 3, 1, 1), (64, 7, 7, 512, 512, 3, 1, 1)],
+                         ids=lambda s: "-".join(map(str, s)))
+def test_bconv2d_bnsign_four_wavefront_kernel(dabnn, oracle, option, shape):
+    """8 words per pixel: the fused threshold epilogue of the kernel whose four wavefronts share a
+    channel group (the default from three groups per CU on; forced here for the small shapes)."""
+    option(dabnn.OPT_AREG_SPLIT, 8)
+    test_bconv2d_bnsign(dabnn, oracle, shape)
+
+
 def test_bnsign_chain_feeds_next_layer(dabnn, oracle):
     """Two fused layers back to back: the packed output of the first is the packed input of the
     second, with no int32 tensor and no bit-pack pass in between."""
