@@ -358,6 +358,8 @@ ODD_SHAPES = [  # N, H, W, Cin, Cout, k, stride, pad
     (2, 11, 7, 128, 20, 3, 2, 1),
     (1, 20, 20, 256, 12, 3, 1, 0),
     (70, 3, 3, 64, 8, 3, 1, 1),
+    # images smaller than the kernel: most taps (or all but one) lie in the padding
+    (4, 1, 1, 64, 64, 3, 1, 1), (1, 1, 5, 128, 16, 3, 2, 1), (3, 2, 1, 64, 4, 3, 1, 2), (2, 1, 1, 512, 32, 3, 1, 1),
 ]
 
 

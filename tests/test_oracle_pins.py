@@ -245,6 +245,19 @@ def test_xor_popcount_identity(oracle, Cin):
         assert int(y[0, ho, wo, co]) == K - 2 * diff
 
 
+@pytest.mark.parametrize("Cin,Cout", [(64, 64), (80, 5), (512, 32)])
+def test_one_pixel_image_closed_form(oracle, Cin, Cout):
+    """A 1x1 image under a 3x3 kernel with pad 1: eight taps lie in the +1 padding, so
+    y = (sum of all weights' signs) - (sum of the centre tap's) + <a, w_centre> (Sec. 2.1.2's
+    convolution with the padding value of the benchmark definition)."""
+    x = wl.activations((4, 1, 1, Cin), 610 + Cin)
+    w = wl.weights((Cout, 3, 3, Cin), 611 + Cin)
+    sx = np.where(np.signbit(x), -1, 1).astype(np.int64)[:, 0, 0, :]
+    sw = np.where(np.signbit(w), -1, 1).astype(np.int64)
+    want = sx @ sw[:, 1, 1, :].T + (sw.sum(axis=(1, 2, 3)) - sw[:, 1, 1, :].sum(axis=1))[None, :]
+    assert np.array_equal(oracle.bconv2d(x, w, 1, 1)[:, 0, 0, :], want.astype(np.int32))
+
+
 def test_bconv2d_at_matches_full(oracle):
     N, H, W, Cin, Cout, k, s, p = 2, 9, 7, 80, 6, 3, 2, 1
     A = oracle.sign(wl.activations((N, H, W, Cin), 81))
