@@ -3,7 +3,10 @@
 #include "bconv_areg_split_kernel.h"
 
 namespace dabnn {
-DABNN_DEFINE_SPLIT_ENTRY_POINT(2, )
+// (a tensor of exactly 8 words per pixel, the Bi-Real-18 case, takes the instantiation with
+// compile-time filter strides)
+DABNN_DEFINE_SPLIT_ENTRY_POINT(2, if (cw_total == 8 && word0 == 0 && active_waves == 4)
+                                      return launch_split_inst<2, false, false, 8>(L, s, stream);)
 
 // 8 words per pixel with the fused threshold epilogue: one launch covers all words.
 hipError_t launch_split_bits_cw2(const uint32_t* a, const uint32_t* w, uint64_t* out,
@@ -11,6 +14,6 @@ hipError_t launch_split_bits_cw2(const uint32_t* a, const uint32_t* w, uint64_t*
                                  hipStream_t stream)
 {
     const SplitLaunch L{a, w, reinterpret_cast<int32_t*>(out), 8, 0, true, 4, thr, flip};
-    return launch_split_inst<2, false, true>(L, s, stream);
+    return launch_split_inst<2, false, true, 8>(L, s, stream);
 }
 }  // namespace dabnn

@@ -59,13 +59,32 @@ struct SplitGeom {
 // that the filter tensor stays below 4 GiB).  The offsets are made opaque per unit, so that each
 // unit forms its few offsets where it uses them: shared between units, the compiler would keep
 // some two hundred of them live and spill scalar registers.
-template <int CWC, int UNIT, int SB>
+// CWT > 0: the launch covers a tensor of exactly CWT words per pixel, so the filter strides are
+// compile-time constants and every load is "row pointer + immediate offset" -- no scalar
+// arithmetic per load (the run-time strides cost some 36 scalar instructions per unit, which at 8
+// words per pixel kept the CU's scalar unit half busy).
+template <int CWC, int UNIT, int CWT, int SB>
 __device__ __forceinline__ void split_load_unit(uint32_t (&sb)[SB], const uint32_t* __restrict__ wq,
                                                 int cout0, int fs, int ts)
 {
     using G = SplitGeom<CWC>;
     constexpr int quad = UNIT / G::CHUNKS;
     constexpr int chunk = UNIT % G::CHUNKS;
+    if constexpr (CWT > 0) {
+        constexpr int FS = 72 * CWT, TS = 8 * CWT;   // bytes per filter, bytes per tap
+        const char* rowp = reinterpret_cast<const char*>(wq) + static_cast<size_t>(cout0 + 4 * quad) * FS;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int d = 0; d < kDC; d += 2) {
+                const int f = chunk * kDC + d;
+                const uint2 u = *reinterpret_cast<const uint2*>(rowp + q * FS + (f / G::D) * TS + (f % G::D) * 4);
+                sb[q * kDC + d] = u.x;
+                sb[q * kDC + d + 1] = u.y;
+            }
+        }
+        return;
+    }
     uint32_t row = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cout0 + 4 * quad) *
                                                   static_cast<uint32_t>(fs));   // (uniform)
     asm volatile("" : "+s"(row), "+s"(fs), "+s"(ts));   // (fs, ts: by-value copies of this call)
@@ -102,7 +121,7 @@ __device__ __forceinline__ void split_compute_unit(const uint32_t (&sb)[SB], int
 // = (y < thr[c]) XOR flip bit c: after the reduction lane (P, j) holds channels 4j..4j+3 of pixel
 // P, forms their four bits, the four lanes of a pixel OR theirs together (two DPP quad permutes)
 // and one of them stores the group's 16 bits.
-template <int CWC, bool PARTIAL, bool BITS = false>
+template <int CWC, bool PARTIAL, bool BITS = false, int CWT = 0>
 __global__ __launch_bounds__(256) void bconv3x3_areg_split_kernel(
     const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, int32_t* __restrict__ y,
     const SplitArgs p)
@@ -175,7 +194,7 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_split_kernel(
     uint32_t sb0[G::SB], sb1[G::SB];
     if (active) {
         load_window(tile);
-        split_load_unit<CWC, 0>(sb0, wq, cgi * CG, filter_bytes, tap_bytes);
+        split_load_unit<CWC, 0, CWT>(sb0, wq, cgi * CG, filter_bytes, tap_bytes);
     }
 
     for (; g < g_end; ++g) {
@@ -198,12 +217,12 @@ __global__ __launch_bounds__(256) void bconv3x3_areg_split_kernel(
                 schedule_fence();
                 if constexpr (u + 1 < G::UNITS) {
                     if constexpr (u % 2 == 0)
-                        split_load_unit<CWC, u + 1>(sb1, wq, cgi * CG, filter_bytes, tap_bytes);
+                        split_load_unit<CWC, u + 1, CWT>(sb1, wq, cgi * CG, filter_bytes, tap_bytes);
                     else
-                        split_load_unit<CWC, u + 1>(sb0, wq, cgi * CG, filter_bytes, tap_bytes);
+                        split_load_unit<CWC, u + 1, CWT>(sb0, wq, cgi * CG, filter_bytes, tap_bytes);
                 } else {
                     if (g + 1 < g_end)  // first unit of the next group (UNITS is even: buffer 0)
-                        split_load_unit<CWC, 0>(sb0, wq, ncgi * CG, filter_bytes, tap_bytes);
+                        split_load_unit<CWC, 0, CWT>(sb0, wq, ncgi * CG, filter_bytes, tap_bytes);
                 }
                 schedule_fence();
                 if constexpr (u % 2 == 0)
@@ -293,10 +312,10 @@ struct SplitLaunch {
     const uint64_t* flip = nullptr;
 };
 
-template <int CWC, bool PARTIAL, bool BITS = false>
+template <int CWC, bool PARTIAL, bool BITS = false, int CWT = 0>
 hipError_t launch_split_inst(const SplitLaunch& L, const ConvShape& s, hipStream_t stream)
 {
-    auto kernel = bconv3x3_areg_split_kernel<CWC, PARTIAL, BITS>;
+    auto kernel = bconv3x3_areg_split_kernel<CWC, PARTIAL, BITS, CWT>;
     static const int blocks_per_cu = resident_blocks_per_cu(kernel);
     const int64_t total_pix = static_cast<int64_t>(s.N) * s.Ho * s.Wo;
     const int64_t tiles = (total_pix + 63) / 64;
