@@ -41,7 +41,7 @@ INFINITY_CACHE_BYTES = 256e6
 # HBM bytes per step (16 launches each) at batch 256, from two rocprofv3 --pmc runs (FETCH_SIZE,
 # then WRITE_SIZE) scaled by a plain 1 GiB copy; see profiles/bireal18_b256_hbm_traffic.md.
 # Algorithmic: conv 1.597e9 (56 MB read + 1541 MB written), bit-pack 1.775e9.
-MEASURED_TRAFFIC_B256 = {"bconv": 1.903e9, "bitpack": 1.775e9}
+MEASURED_TRAFFIC_B256 = {"bconv": 1.904e9, "bitpack": 1.775e9}
 
 
 def main():
