@@ -147,9 +147,9 @@ hipError_t launch_bconv_areg(const uint64_t* a, const uint64_t* w, int32_t* y, c
         return hipErrorNotSupported;
     const uint32_t* a32 = reinterpret_cast<const uint32_t*>(a);
     const uint32_t* w32 = reinterpret_cast<const uint32_t*>(w);
-    // 8 words per pixel: both kernel kinds take the same time at batch 256 (62 us per 59 G-op
-    // layer); the four-wavefront kernel writes whole 64-byte runs where the one-wavefront kernel's
-    // direct stores cost 2.25 times the output bytes in HBM writes, so it is the default there.
+    // 8 words per pixel: the four-wavefront kernel is the faster one at batch 256 (55 against 57 us
+    // per 59 G-op layer) and writes whole 64-byte runs where the one-wavefront kernel's direct
+    // stores cost 2.25 times the output bytes in HBM writes, so it is the default there.
     // Option DABNN_OPT_AREG_SPLIT: 4 forces it for 4 words as well, 1 never uses it below 9 words.
     const int split_option = option(DABNN_OPT_AREG_SPLIT);
     const bool split_fits = s.Cw % 4 == 0 && s.Cout % 16 == 0 && option(DABNN_OPT_AREG_STORE) != 1;
