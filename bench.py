@@ -442,6 +442,19 @@ def other_configs(binding, wl, np, torch, launch_us, graph_us, want_oracle):
         rows.append(row)
         del xg, o
     out["cfg3_bitpack"] = rows
+    # The same ragged channel counts on tensors far beyond the Infinity Cache: the HBM figure of
+    # the bit-pack kernel for channel counts that are no multiple of 64 (device-generated input).
+    rows = []
+    for shape in ((256, 56, 56, 80), (256, 56, 56, 200), (256, 56, 56, 65)):
+        xg = torch.empty(shape, dtype=torch.float32, device="cuda").normal_()
+        o = torch.empty(shape[:-1] + ((shape[-1] + 63) // 64,), dtype=torch.int64, device="cuda")
+        med, _ = launch_us(lambda: binding.bitpack(xg, out=o))
+        moved = xg.numel() * 4 + o.numel() * 8
+        rows.append({"shape": "x".join(map(str, shape)), "MB_moved": round(moved / 1e6, 1), "us": round(med, 2),
+                     "GBps": round(moved / med / 1e3, 1),
+                     "frac_of_hbm_peak": round(moved / med / 1e3 / HBM_PEAK_GBPS, 4)})
+        del xg, o
+    out["bitpack_ragged_channels_large"] = rows
     out["other_word_counts"] = [word_count_row(c) for c in (160, 320, 384, 448, 1024)]
     return out
 
